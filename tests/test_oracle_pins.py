@@ -1,0 +1,409 @@
+"""CPU pins for the oracle: what the paper and the mathematics fix, checked
+against oracle/qn_oracle.c.  None of these use the GPU or the HIP library.
+
+Each test names the plausible oracle mistake it would catch.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+rng0 = np.random.default_rng(12345)
+
+
+# --------------------------------------------------------------------------
+# helpers that build inputs only (no method arithmetic beyond numpy library
+# calls used as independent references)
+# --------------------------------------------------------------------------
+def quadratic_workers(A, b, thetas):
+    """grad_k = A theta_k - b for a dense SPD A; thetas has shape (m, n)."""
+    return thetas @ A.T - b[None, :]
+
+
+def random_spd(n, rng, lo=0.5, hi=4.0):
+    Q, _ = np.linalg.qr(rng.standard_normal((n, n)))
+    return (Q * np.linspace(lo, hi, n)) @ Q.T
+
+
+def centred_basis(m, rng):
+    """m x (m-1) orthonormal basis of the complement of the all-ones vector."""
+    M = rng.standard_normal((m, m))
+    M[:, 0] = 1.0
+    Q, _ = np.linalg.qr(M)
+    return Q[:, 1:]
+
+
+def engineered(n, m, svals, rng):
+    """Worker matrices whose centred gradient matrix G has exactly the given
+    m-1 singular values: G = U diag(s) W^T with W orthonormal and W^T 1 = 0."""
+    s = np.asarray(svals, float)
+    assert s.shape == (m - 1,)
+    U, _ = np.linalg.qr(rng.standard_normal((n, m - 1)))
+    W = centred_basis(m, rng)
+    G = (U * s) @ W.T                       # n x m, rows sum to zero
+    gbar = rng.standard_normal(n)
+    grads = (G + gbar[:, None]).T           # (m, n)
+    thetas = rng.standard_normal((m, n)) * 0.1 + rng.standard_normal(n)[None, :]
+    return np.ascontiguousarray(thetas), np.ascontiguousarray(grads), U, W
+
+
+# --------------------------------------------------------------------------
+# element widening, means, centring, Gram: hand values
+# --------------------------------------------------------------------------
+def test_bf16_widening_exact():
+    # catches: wrong shift / endianness in the bfloat16 reader
+    bits = np.array([[0x3F80, 0xC000, 0x3FC0, 0x0000, 0xBE80]], np.uint16)
+    got = oracle.row_means(bits)            # m = 1: the mean is the value
+    assert got.tolist() == [1.0, -2.0, 1.5, 0.0, -0.25]
+
+
+def test_means_and_centre_hand_values():
+    # catches: mean over parameters instead of over workers, wrong divisor
+    X = np.array([[1.0, 2.0, 3.0], [3.0, 6.0, 9.0], [5.0, 1.0, 0.0]])
+    mean = oracle.row_means(X)
+    assert np.array_equal(mean, [3.0, 3.0, 4.0])
+    Xc = oracle.centre(X, mean)
+    assert np.array_equal(Xc, [[-2, -1, -1], [0, 3, 5], [2, -2, -4]])
+    # strided chunk (ld > rows) reads the right elements
+    assert np.array_equal(oracle.row_means(X[:, 1:]), [3.0, 4.0])
+
+
+def test_gram_and_gemv_hand_values():
+    # catches: transposed operand (G G^T), dropped term, wrong index
+    G = np.array([[1.0, 0.0, 2.0], [0.0, 3.0, -1.0]])   # g_1, g_2 as rows
+    C = oracle.gram(G)
+    assert np.array_equal(C, [[5.0, -2.0], [-2.0, 10.0]])
+    w = oracle.gemv_t(G, np.array([1.0, 1.0, 1.0]))
+    assert np.array_equal(w, [3.0, 2.0])
+
+
+def test_f32_input_is_read_not_rounded_again():
+    X = rng0.standard_normal((3, 50)).astype(np.float32)
+    assert np.array_equal(oracle.row_means(X),
+                          oracle.row_means(X.astype(np.float64)))
+
+
+# --------------------------------------------------------------------------
+# eigen-solver: closed form and library routine
+# --------------------------------------------------------------------------
+def test_jacobi_2x2_closed_form():
+    mu, V, _ = oracle.jacobi_eigh(np.array([[2.0, 1.0], [1.0, 2.0]]))
+    assert np.allclose(mu, [3.0, 1.0], atol=1e-15)
+    s = 1 / np.sqrt(2)
+    assert np.allclose(np.abs(V[0]), [s, s]) and V[0][0] * V[0][1] > 0
+    assert np.allclose(np.abs(V[1]), [s, s]) and V[1][0] * V[1][1] < 0
+
+
+@pytest.mark.parametrize("m", [1, 2, 3, 4, 7, 8, 16, 31, 32])
+def test_jacobi_vs_library_eigh(m):
+    # catches: wrong rotation sign / angle, unsorted output, V not carried
+    rng = np.random.default_rng(m)
+    X = rng.standard_normal((m + 5, m))
+    for C in (X.T @ X,                                    # PSD Gram
+              (lambda S: S + S.T)(rng.standard_normal((m, m)))):  # indefinite
+        mu, V, sweeps = oracle.jacobi_eigh(C)
+        ref = np.linalg.eigvalsh(C)[::-1]
+        scale = max(np.abs(ref).max(), 1e-300)
+        assert np.abs(mu - ref).max() <= 1e-13 * scale
+        assert np.all(np.diff(mu) <= 0)
+        Vc = V.T                                          # columns = v_k
+        assert np.abs(Vc.T @ Vc - np.eye(m)).max() <= 1e-13
+        assert np.abs(C @ Vc - Vc * mu).max() <= 1e-12 * scale
+        assert 0 <= sweeps <= 20
+
+
+def test_jacobi_degenerate_cluster_and_zero():
+    mu, V, _ = oracle.jacobi_eigh(np.zeros((5, 5)))
+    assert np.array_equal(mu, np.zeros(5))
+    assert np.array_equal(V, np.eye(5))
+    # flat spectrum with an exact null vector (what centred iid workers give)
+    m = 8
+    W = centred_basis(m, np.random.default_rng(3))
+    C = 4.0 * W @ W.T
+    mu, V, _ = oracle.jacobi_eigh(C)
+    assert np.allclose(mu[:-1], 4.0, atol=1e-13) and abs(mu[-1]) <= 1e-14
+    assert abs(abs(V[-1] @ np.ones(m)) - np.sqrt(m)) <= 1e-12
+
+
+def test_sigma_is_sqrt_of_eigenvalue_clamped():
+    s = oracle.sigma_from_mu(np.array([9.0, 4.0, 0.0, -1e-18]))
+    assert s.tolist() == [3.0, 2.0, 0.0, 0.0]
+
+
+# --------------------------------------------------------------------------
+# cutoff rule (golden fixture)
+# --------------------------------------------------------------------------
+def _cutoff_cases():
+    out = []
+    with open(os.path.join(GOLDEN, "cutoff_cases.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            lam, sig, j = [p.strip() for p in line.split("|")]
+            out.append((float(lam), [float(x) for x in sig.split()], int(j)))
+    return out
+
+
+@pytest.mark.parametrize("lam,sig,j", _cutoff_cases())
+def test_cutoff_rule_golden(lam, sig, j):
+    # catches: strict instead of inclusive compare, comparing eigenvalues of
+    # G^T G against lambda instead of singular values, off-by-one
+    assert oracle.select_j(sig, lam) == j
+
+
+def test_cutoff_uses_singular_values_not_eigenvalues():
+    # sigma = (1, 0.3): lambda = 0.2 keeps both; on eigenvalues (1, 0.09) a
+    # wrong reading would keep one
+    n, m = 40, 3
+    th, gr, _, _ = engineered(n, m, [1.0, 0.3], np.random.default_rng(5))
+    r = oracle.update_literal(th, gr, 1.0, 0.2)
+    assert r["j"] == 2
+    assert np.allclose(r["sigma"], [1.0, 0.3, 0.0], atol=1e-12)
+    assert oracle.update_literal(th, gr, 1.0, 0.31)["j"] == 1
+
+
+# --------------------------------------------------------------------------
+# hand-worked step (golden fixture)
+# --------------------------------------------------------------------------
+def _hand():
+    d = {}
+    with open(os.path.join(GOLDEN, "hand_worked_step.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            parts = [p.strip() for p in line.split("|")]
+            rows = [[float(x) for x in p.split()] for p in parts[1:]]
+            d[parts[0]] = rows
+    return d
+
+
+def test_hand_worked_step_literal_and_streaming():
+    h = _hand()
+    th = np.array(h["thetas"])
+    gr = np.array(h["grads"])
+    lam = h["lambda"][0][0]
+    for tau_key, out_key in (("tau", "theta_new"), ("tau2", "theta_new2")):
+        tau = h[tau_key][0][0]
+        for r in (oracle.update_literal(th, gr, tau, lam),
+                  oracle.update_streaming(th, gr, tau, lam)):
+            assert r["j"] == int(h["j"][0][0])
+            assert np.allclose(r["theta_new"], h[out_key][0], atol=1e-14)
+            assert np.allclose(r["sigma"], h["sigma"][0], atol=1e-14)
+            assert np.allclose(r["C"], np.array(h["C"]), atol=1e-14)
+            assert np.allclose(r["w"], h["w"][0], atol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# T1: j = 0 is averaged SGD
+# --------------------------------------------------------------------------
+def test_j0_is_averaged_sgd():
+    # catches: correction applied when j = 0, wrong sign of tau, mean misuse
+    rng = np.random.default_rng(7)
+    m, n, tau = 5, 300, 0.37
+    th = rng.standard_normal((m, n))
+    gr = rng.standard_normal((m, n))
+    sgd = th.mean(0) - tau * gr.mean(0)
+    for fn in (oracle.update_literal, oracle.update_streaming):
+        r = fn(th, gr, tau, 1.5)                 # lambda > 1: nothing passes
+        assert r["j"] == 0
+        assert np.abs(r["theta_new"] - sgd).max() <= 1e-15
+        # identical grads: sigma_1 = 0.  Stored fp32 values, as the device
+        # library sees them: m*x and (m*x)/m are then exact in double, so the
+        # centred matrix is exactly zero.
+        th32 = th.astype(np.float32)
+        same = np.repeat(gr[:1], m, axis=0).astype(np.float32)
+        r = fn(th32, same, tau, 0.1)
+        assert r["j"] == 0
+        ref = th32.astype(np.float64).mean(0) - tau * same[0].astype(np.float64)
+        assert np.abs(r["theta_new"] - ref).max() <= 1e-15
+        r = fn(th[:1], gr[:1], tau, 0.1)         # a single worker
+        assert r["j"] == 0
+        assert np.abs(r["theta_new"] - (th[0] - tau * gr[0])).max() <= 1e-15
+
+
+# --------------------------------------------------------------------------
+# T2 / T3: the two branches of eq. (3)
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("lam,expect_j", [(1e-6, 5), (0.42, 3), (0.95, 1)])
+def test_secant_inverse_on_span_and_identity_off_span(lam, expect_j):
+    rng = np.random.default_rng(11)
+    n, m = 60, 6
+    th, gr, U, W = engineered(n, m, [2.0, 1.0, 0.9, 0.4, 0.2], rng)
+    theta_bar = oracle.row_means(th)
+    g_bar = oracle.row_means(gr)
+    Theta = oracle.centre(th, theta_bar)
+    G = oracle.centre(gr, g_bar)
+    mu, V, _ = oracle.jacobi_eigh(oracle.gram(G))
+    sigma = oracle.sigma_from_mu(mu)
+    j = oracle.select_j(sigma, lam)
+    assert j == expect_j
+    for k in range(j):
+        # catches: 1/sigma_k^2 or no 1/sigma_k in eq. (4), y_k built from G
+        z = G.T @ V[k]
+        out = oracle.apply_Hinv_literal(Theta, G, sigma, V, j, z)
+        assert np.abs(out - Theta.T @ V[k]).max() <= 1e-12
+    for k in range(j, m - 1):
+        # a dropped direction is in the complement: passes through unchanged
+        z = G.T @ V[k]
+        out = oracle.apply_Hinv_literal(Theta, G, sigma, V, j, z)
+        assert np.abs(out - z).max() <= 1e-12
+    # random z projected off u_1..u_j (U's first j columns span the same space)
+    z = rng.standard_normal(n)
+    z -= U[:, :j] @ (U[:, :j].T @ z)
+    out = oracle.apply_Hinv_literal(Theta, G, sigma, V, j, z)
+    assert np.abs(out - z).max() <= 1e-12
+
+
+# --------------------------------------------------------------------------
+# T4: exact quadratic, n = m - 1: the step lands on the minimiser
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("m", [3, 4, 8, 17, 32])
+def test_exact_quadratic_lands_on_minimiser(m):
+    # catches: any error in the chain means -> Gram -> eig -> eq. (4) -> eq. (2)
+    rng = np.random.default_rng(100 + m)
+    n = m - 1
+    A = random_spd(n, rng)
+    b = rng.standard_normal(n)
+    th = rng.standard_normal(n)[None, :] + 0.3 * rng.standard_normal((m, n))
+    gr = quadratic_workers(A, b, th)
+    xstar = np.linalg.solve(A, b)
+    for fn in (oracle.update_literal, oracle.update_streaming):
+        r = fn(th, gr, 1.0, 1e-6)
+        assert r["j"] == n
+        assert np.abs(r["theta_new"] - xstar).max() <= 1e-9 * np.abs(xstar).max()
+        # damped step: theta_bar - tau (theta_bar - x*)
+        r = fn(th, gr, 0.25, 1e-6)
+        tb = th.mean(0)
+        assert np.abs(r["theta_new"] - (tb - 0.25 * (tb - xstar))).max() <= 1e-9
+
+
+def test_quadratic_tall_case_newton_on_span_sgd_off_span():
+    # n > m-1, exact quadratic with A = s*I: G = s*Theta so H^-1 acts as 1/s on
+    # span(G) and as the identity elsewhere.
+    rng = np.random.default_rng(21)
+    n, m, s, tau = 50, 5, 4.0, 1.0
+    th = rng.standard_normal(n)[None, :] + 0.1 * rng.standard_normal((m, n))
+    b = rng.standard_normal(n)
+    gr = s * th - b
+    r = oracle.update_literal(th, gr, tau, 1e-6)
+    assert r["j"] == m - 1
+    tb, gb = th.mean(0), gr.mean(0)
+    Q, _ = np.linalg.qr((th - tb).T)             # basis of span(Theta) = span(G)
+    Q = Q[:, :m - 1]
+    on = Q @ (Q.T @ gb)
+    expect = tb - tau * ((gb - on) + on / s)
+    assert np.abs(r["theta_new"] - expect).max() <= 1e-12
+
+
+# --------------------------------------------------------------------------
+# independent route: explicit n x n operator from a library SVD of G
+# --------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(4))
+def test_dense_operator_from_library_svd(seed):
+    rng = np.random.default_rng(seed)
+    n, m, tau, lam = 12, 5, 0.8, 0.3
+    th = rng.standard_normal((m, n))
+    gr = rng.standard_normal((m, n)) * np.linspace(0.2, 3, n)[None, :]
+    tb, gb = th.mean(0), gr.mean(0)
+    Theta, G = (th - tb).T, (gr - gb).T                   # n x m
+    U, S, Vt = np.linalg.svd(G, full_matrices=False)
+    j = int(np.sum(S >= lam * S[0]))
+    Uj = U[:, :j]
+    Hinv = (np.eye(n) - Uj @ Uj.T) + Theta @ Vt[:j].T @ np.diag(1 / S[:j]) @ Uj.T
+    expect = tb - tau * Hinv @ gb
+    for fn in (oracle.update_literal, oracle.update_streaming):
+        r = fn(th, gr, tau, lam)
+        assert r["j"] == j
+        assert np.abs(r["theta_new"] - expect).max() <= 1e-12
+        # the null singular value is only resolved to sqrt(eps) through G^T G
+        assert np.allclose(r["sigma"][:-1], S[:-1], atol=1e-12)
+        assert r["sigma"][-1] <= 1e-6 * S[0]
+
+
+# --------------------------------------------------------------------------
+# T5: literal eq. (4) == closed form, on the workload generators and dtypes
+# --------------------------------------------------------------------------
+def _workload_np(name, n):
+    import torch  # generator module needs torch; CPU only here
+    from paper_1709_05069_amd import synth
+    wl = synth.WORKLOADS[name].scaled(n)
+    th, gr = synth.make_worker_states(wl, "cpu")
+    return wl, synth.to_numpy_stored(th), synth.to_numpy_stored(gr)
+
+
+@pytest.mark.parametrize("name,n", [("tiny_exact", 4096), ("small_mlp", 30011),
+                                    ("resnet50", 20000), ("gpt2_small", 9001),
+                                    ("stress_1b_bf16", 8192)])
+def test_literal_equals_closed_form_on_workloads(name, n):
+    wl, th, gr = _workload_np(name, n)
+    a = oracle.update_literal(th, gr, wl.tau, wl.lam)
+    b = oracle.update_streaming(th, gr, wl.tau, wl.lam, chunk_rows=4099)
+    assert a["j"] == b["j"] == wl.m - 1       # flat spectrum, one null direction
+    num = np.linalg.norm(a["theta_new"] - b["theta_new"])
+    assert num <= 1e-12 * np.linalg.norm(a["theta_new"])
+    assert np.abs(a["C"] - b["C"]).max() <= 1e-11 * np.abs(a["C"]).max()
+    assert np.abs(a["w"] - b["w"]).max() <= 1e-10 * np.abs(a["w"]).max()
+
+
+def test_tiny_exact_config_facts():
+    wl, th, gr = _workload_np("tiny_exact", 4096)
+    r = oracle.update_streaming(th, gr, wl.tau, wl.lam)
+    assert r["j"] == 3
+    assert r["sigma"][3] <= 1e-6 * r["sigma"][0]
+    # margin of the cutoff decision is wide on this workload
+    assert r["sigma"][2] / r["sigma"][0] > 10 * wl.lam
+
+
+# --------------------------------------------------------------------------
+# T6: structural invariants
+# --------------------------------------------------------------------------
+def test_structural_invariants():
+    wl, th, gr = _workload_np("small_mlp", 20000)
+    r = oracle.update_streaming(th, gr, wl.tau, wl.lam)
+    m = wl.m
+    C, w, c = r["C"], r["w"], r["c"]
+    scale = np.abs(C).max()
+    assert np.abs(C - C.T).max() <= 1e-12 * scale
+    assert np.abs(C @ np.ones(m)).max() <= 1e-10 * scale      # G 1 = 0
+    assert abs(w.sum()) <= 1e-10 * np.abs(w).max()
+    assert abs(c.sum()) <= 1e-8 * np.abs(c).max()
+    assert np.linalg.eigvalsh(C).min() >= -1e-10 * scale       # PSD
+    assert r["j"] <= m - 1
+    assert np.all(np.diff(r["sigma"]) <= 0) and np.all(r["sigma"] >= 0)
+
+
+# --------------------------------------------------------------------------
+# T8: metamorphic relations
+# --------------------------------------------------------------------------
+def test_metamorphic_relations():
+    rng = np.random.default_rng(31)
+    n, m, tau, lam = 200, 6, 0.6, 0.35
+    th, gr, _, _ = engineered(n, m, [3.0, 2.0, 1.5, 0.7, 0.3], rng)
+    base = oracle.update_literal(th, gr, tau, lam)
+    assert 0 < base["j"] < m - 1
+    # permuting workers changes nothing
+    p = rng.permutation(m)
+    r = oracle.update_literal(th[p], gr[p], tau, lam)
+    assert r["j"] == base["j"]
+    assert np.abs(r["theta_new"] - base["theta_new"]).max() <= 1e-12
+    # translating every theta_k by d translates theta_new by d
+    d = rng.standard_normal(n)
+    r = oracle.update_literal(th + d, gr, tau, lam)
+    assert np.abs(r["theta_new"] - (base["theta_new"] + d)).max() <= 1e-12
+    # translating every grad_k by d leaves G alone; the step is linear in g_bar
+    r = oracle.update_literal(th, gr + d, tau, lam)
+    tb, gb = oracle.row_means(th), oracle.row_means(gr)
+    Theta, G = oracle.centre(th, tb), oracle.centre(gr, gb)
+    Hd = oracle.apply_Hinv_literal(Theta, G, base["sigma"], base["V"],
+                                   base["j"], d)
+    assert r["j"] == base["j"]
+    assert np.abs(r["theta_new"] - (base["theta_new"] - tau * Hd)).max() <= 1e-11
+    # scaling all gradients by s scales sigma by s and H^-1 on the span by 1/s
+    r = oracle.update_literal(th, 2.0 * gr, tau, lam)
+    assert r["j"] == base["j"]
+    assert np.allclose(r["sigma"], 2.0 * base["sigma"], rtol=1e-12, atol=1e-14)
