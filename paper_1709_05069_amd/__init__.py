@@ -1,0 +1,12 @@
+"""MI355X (gfx950) implementation of the server-side quasi-Newton step of
+Arnold & Wang, "Accelerating SGD for Distributed Deep-Learning Using
+Approximated Hessian Matrix" (Section 2, eq. (2)-(4)).
+
+`qn` is a thin binding over the C ABI of libqn.so (include/qn.h): it only
+marshals torch tensors into device pointers.  `synth` generates the seeded
+synthetic worker states.  There is no CPU fallback: every call fails loudly
+when the HIP library has not been built.
+"""
+from . import synth  # noqa: F401
+from .qn import (qn_update, qn_gram, qn_eig, qn_apply, qn_init,  # noqa: F401
+                 trace_begin, trace_end, KERNEL_NAMES, QnError)

@@ -1,0 +1,53 @@
+"""Loads libqn.so (built in-tree by paper_1709_05069_amd/build.py)."""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libqn.so")
+
+_i64 = ctypes.c_int64
+_int = ctypes.c_int
+_f32 = ctypes.c_float
+_vp = ctypes.c_void_p
+
+# name -> (restype, argtypes); mirrors include/qn.h
+SIGNATURES = {
+    "qn_status_string": (ctypes.c_char_p, [_int]),
+    "qn_kernel_name": (ctypes.c_char_p, [_int]),
+    "qn_init": (_int, []),
+    "qn_shutdown": (_int, []),
+    "qn_update": (_int, [_vp, _vp, _i64, _int, _f32, _f32, _vp, _vp, _vp]),
+    "qn_update_bf16": (_int, [_vp, _vp, _i64, _int, _f32, _f32, _vp, _vp, _vp]),
+    "qn_gram": (_int, [_vp, _i64, _int, _vp, _vp, _vp]),
+    "qn_gram_bf16": (_int, [_vp, _i64, _int, _vp, _vp, _vp]),
+    "qn_eig": (_int, [_vp, _vp, _int, _f32, _vp, _vp, _vp, _vp, _vp]),
+    "qn_apply": (_int, [_vp, _vp, _i64, _int, _vp, _f32, _vp, _vp]),
+    "qn_apply_bf16": (_int, [_vp, _vp, _i64, _int, _vp, _f32, _vp, _vp]),
+    "qn_update_ex": (_int, [_vp, _vp, _int, _i64, _int, _i64, _f32, _f32, _vp,
+                            _vp, _vp]),
+    "qn_gram_ex": (_int, [_vp, _int, _i64, _int, _i64, _vp, _vp, _vp]),
+    "qn_apply_ex": (_int, [_vp, _vp, _int, _i64, _int, _i64, _vp, _f32, _vp,
+                           _vp]),
+    "qn_trace_begin": (_int, [_int]),
+    "qn_trace_end": (_int, [_vp, _vp]),
+}
+
+_LIB = None
+
+
+def load():
+    """Returns the ctypes handle; raises if the library has not been built."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first "
+                "(python -m paper_1709_05069_amd.build). "
+                "There is no fallback path.")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(lib, name)   # AttributeError if a symbol is missing
+            fn.restype = res
+            fn.argtypes = args
+        _LIB = lib
+    return _LIB

@@ -1,0 +1,195 @@
+// theta_new = theta_bar - tau * ( g_bar + (Theta - G) c )         (eq. (2) with
+// eq. (4) applied to z = g_bar; Theta, G are the centred worker matrices of
+// Section 2 and c the coefficient vector produced by the eigen step).
+//
+// One streaming pass: every row needs its 2m inputs once and produces one
+// output, about half a flop per byte, so the kernel is bound by HBM bandwidth.
+// Lane = rows (128-bit loads along each worker's contiguous column), all m
+// values of a row meet in one lane, so the row means cost nothing extra.
+//
+// Arithmetic per row i, with the pivots p = theta_0[i], r = grad_0[i] and the
+// differences t_k = theta_k[i] - p, h_k = grad_k[i] - r (exact or correctly
+// rounded; same magnitude as the centred entries, so no cancellation later):
+//     theta_bar = p + St/m,  g_bar = r + Sh/m,        St = sum t_k, Sh = sum h_k
+//     (Theta - G) c = sum_k c_k (t_k - h_k) - (St - Sh)/m * sum_k c_k
+// which equals the centred definition for any c (the last term vanishes when
+// the entries of c sum to zero, as they do when c comes from the eigen step).
+#include "qn_internal.h"
+
+namespace qn {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+
+constexpr int kApplyThreads = 256;
+constexpr int kApplyChunk = 8;     // worker columns whose loads are issued together
+
+template <int DT, int R>
+__device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (&x)[R])
+{
+    if constexpr (DT == QN_F32) {
+        const float *p = static_cast<const float *>(base) + elem;
+        if constexpr (R == 4) {
+            const v4f v = *reinterpret_cast<const v4f *>(p);
+            x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+        } else {
+            static_assert(R == 1, "fp32 rows per lane");
+            x[0] = *p;
+        }
+    } else {
+        const uint16_t *p = static_cast<const uint16_t *>(base) + elem;
+        if constexpr (R == 8) {
+            const v4u v = *reinterpret_cast<const v4u *>(p);
+            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                x[2 * h + 0] = __uint_as_float(u[h] << 16);
+                x[2 * h + 1] = __uint_as_float(u[h] & 0xffff0000u);
+            }
+        } else {
+            static_assert(R == 1, "bf16 rows per lane");
+            x[0] = __uint_as_float(static_cast<uint32_t>(*p) << 16);
+        }
+    }
+}
+
+// Processes rows [row, row + R) of every worker column.
+template <int DT, int MC, int R>
+__device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
+                                           const void *__restrict__ grads,
+                                           int64_t row, int m_rt, int64_t ld,
+                                           const float *__restrict__ c,
+                                           float csum, float tau, float inv_m,
+                                           float *__restrict__ out)
+{
+    const int m = MC ? MC : m_rt;
+    float p[R], r[R], st[R], sh[R], acc[R];
+    load_vec<DT, R>(thetas, row, p);
+    load_vec<DT, R>(grads, row, r);
+#pragma unroll
+    for (int e = 0; e < R; ++e) {
+        st[e] = 0.0f;
+        sh[e] = 0.0f;
+        acc[e] = 0.0f;
+    }
+#pragma unroll
+    for (int k0 = 1; k0 < (MC ? MC : QN_MAX_M); k0 += kApplyChunk) {
+        if (k0 >= m)
+            break;
+        float th[kApplyChunk][R], gr[kApplyChunk][R];
+#pragma unroll
+        for (int u = 0; u < kApplyChunk; ++u)
+            if (k0 + u < m) {
+                load_vec<DT, R>(thetas, (k0 + u) * ld + row, th[u]);
+                load_vec<DT, R>(grads, (k0 + u) * ld + row, gr[u]);
+            }
+#pragma unroll
+        for (int u = 0; u < kApplyChunk; ++u)
+            if (k0 + u < m) {
+                const float ck = c[k0 + u];
+#pragma unroll
+                for (int e = 0; e < R; ++e) {
+                    const float t = th[u][e] - p[e];
+                    const float h = gr[u][e] - r[e];
+                    st[e] += t;
+                    sh[e] += h;
+                    acc[e] = fmaf(ck, t - h, acc[e]);
+                }
+            }
+    }
+    float res[R];
+#pragma unroll
+    for (int e = 0; e < R; ++e) {
+        const float mt = st[e] * inv_m, mh = sh[e] * inv_m;
+        const float corr = acc[e] - csum * (mt - mh);
+        res[e] = (p[e] + mt) - tau * ((r[e] + mh) + corr);
+    }
+    if constexpr (R == 1) {
+        out[row] = res[0];
+    } else {
+#pragma unroll
+        for (int e = 0; e < R; e += 4) {
+            v4f v = {res[e], res[e + 1], res[e + 2], res[e + 3]};
+            __builtin_nontemporal_store(v, reinterpret_cast<v4f *>(out + row + e));
+        }
+    }
+}
+
+template <int DT, int MC, bool VEC>
+__global__ __launch_bounds__(kApplyThreads) void apply_kernel(
+    const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
+    int m_rt, int64_t ld, const float *__restrict__ c, float tau,
+    float *__restrict__ out)
+{
+    constexpr int R = VEC ? (DT == QN_F32 ? 4 : 8) : 1;
+    const int m = MC ? MC : m_rt;
+    float csum = 0.0f;
+    for (int k = 0; k < m; ++k)
+        csum += c[k];
+    const float inv_m = 1.0f / static_cast<float>(m);
+
+    const int64_t nvec = n / R;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kApplyThreads;
+    for (int64_t v = static_cast<int64_t>(blockIdx.x) * kApplyThreads + threadIdx.x;
+         v < nvec; v += stride)
+        apply_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, csum, tau, inv_m, out);
+
+    if constexpr (R > 1) {   // rows past the last full vector
+        const int64_t tail0 = nvec * R;
+        if (blockIdx.x == 0 && tail0 + threadIdx.x < n)
+            apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c,
+                                  csum, tau, inv_m, out);
+    }
+}
+
+template <int DT, int MC>
+static void launch_mc(bool vec, int grid, const void *thetas, const void *grads,
+                      int64_t n, int m, int64_t ld, const float *c, float tau,
+                      float *out, hipStream_t stream)
+{
+    if (vec)
+        hipLaunchKernelGGL((apply_kernel<DT, MC, true>), dim3(grid), dim3(kApplyThreads),
+                           0, stream, thetas, grads, n, m, ld, c, tau, out);
+    else
+        hipLaunchKernelGGL((apply_kernel<DT, MC, false>), dim3(grid), dim3(kApplyThreads),
+                           0, stream, thetas, grads, n, m, ld, c, tau, out);
+}
+
+template <int DT>
+static void launch_dt(bool vec, int grid, const void *thetas, const void *grads,
+                      int64_t n, int m, int64_t ld, const float *c, float tau,
+                      float *out, hipStream_t stream)
+{
+    switch (m) {
+    case 4: launch_mc<DT, 4>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
+    case 8: launch_mc<DT, 8>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
+    case 16: launch_mc<DT, 16>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
+    case 32: launch_mc<DT, 32>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
+    default: launch_mc<DT, 0>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
+    }
+}
+
+int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
+                 int m, int64_t ld, const float *c, float tau, float *theta_new,
+                 int cu_count, hipStream_t stream)
+{
+    const size_t esz = dtype == QN_F32 ? 4 : 2;
+    const bool vec = (reinterpret_cast<uintptr_t>(thetas) % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(theta_new) % 16 == 0) &&
+                     ((static_cast<uint64_t>(ld) * esz) % 16 == 0);
+    const int rows_per_thread = vec ? (dtype == QN_F32 ? 4 : 8) : 1;
+    const int64_t per_block = static_cast<int64_t>(kApplyThreads) * rows_per_thread;
+    int64_t want = (n + per_block - 1) / per_block;
+    const int64_t cap = static_cast<int64_t>(cu_count) * 8;
+    const int grid = static_cast<int>(want < cap ? want : cap);
+
+    TraceScope ts(QN_K_APPLY, stream);
+    if (dtype == QN_F32)
+        launch_dt<QN_F32>(vec, grid, thetas, grads, n, m, ld, c, tau, theta_new, stream);
+    else
+        launch_dt<QN_BF16>(vec, grid, thetas, grads, n, m, ld, c, tau, theta_new, stream);
+    return check_launch();
+}
+
+}  // namespace qn

@@ -1,0 +1,64 @@
+// Internal declarations shared by the HIP translation units of libqn.
+// Not part of the public ABI (that is include/qn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qn.h"
+
+namespace qn {
+
+// ---- fixed launch geometry -------------------------------------------------
+// The Gram pass runs a fixed grid so that the summation tree depends only on
+// (n, m, dtype).  Each block writes one partial; the partial holds the raw
+// MFMA accumulator layout: TILE_ENTRIES values per 16x16 tile, up to 3 tiles
+// (the lower triangle of a 2x2 tiling of a 32x32 matrix).
+constexpr int kGramThreads = 256;               // 4 wavefronts
+constexpr int kGramWaves = kGramThreads / 64;
+constexpr int kGramMaxBlocks = 2048;
+constexpr int kTileEntries = 256;               // 16 x 16
+constexpr int kMaxTiles = 3;
+constexpr int kMaxEntries = kTileEntries * kMaxTiles;
+
+// ---- per-device workspace ---------------------------------------------------
+struct Workspace {
+    double *partials;   // kGramMaxBlocks * kMaxEntries
+    double *mraw;       // kMaxEntries: reduced accumulators, raw tile layout
+    double *C;          // QN_MAX_M * QN_MAX_M
+    double *w;          // QN_MAX_M
+    float *c;           // QN_MAX_M
+    void *base;
+    size_t bytes;
+    int cu_count;
+};
+
+// Returns the current device's workspace (allocating it on first use).
+int get_workspace(Workspace **out);
+
+// ---- kernel launchers (each enqueues on `stream`, returns a qn_status) ------
+int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
+                Workspace *ws, double *C, double *w, hipStream_t stream);
+int launch_eig(const double *C, const double *w, int m, float lambda,
+               double *sigma, double *V, float *c, int *j_out,
+               hipStream_t stream);
+int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
+                 int m, int64_t ld, const float *c, float tau, float *theta_new,
+                 int cu_count, hipStream_t stream);
+
+// ---- tracing ------------------------------------------------------------------
+// RAII bracket: records a start/stop event pair around one kernel launch when
+// tracing is enabled; otherwise does nothing.
+struct TraceScope {
+    TraceScope(int kernel_id, hipStream_t stream);
+    ~TraceScope();
+    int slot;
+    hipStream_t stream;
+};
+
+inline int check_launch()
+{
+    return hipGetLastError() == hipSuccess ? QN_OK : QN_ELAUNCH;
+}
+
+}  // namespace qn

@@ -1,0 +1,133 @@
+"""Argument marshalling for libqn's C ABI: torch tensors in, torch tensors out.
+
+Worker matrices are (m, n) tensors whose rows are the workers' vectors
+(stride(1) == 1; stride(0) = ld >= n), dtype float32 or bfloat16, on the HIP
+device.  Every step of the computation runs in the library's kernels; torch
+only owns the memory and the stream.
+"""
+import ctypes
+
+import torch
+
+from . import _lib
+
+QN_F32, QN_BF16 = 0, 1
+KERNEL_NAMES = ("gram_stage1", "gram_reduce", "gram_project", "eig_select",
+                "apply_kernel")
+
+
+class QnError(RuntimeError):
+    pass
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        msg = _lib.load().qn_status_string(rc).decode()
+        raise QnError(f"{what}: {msg} (status {rc})")
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _worker(t: torch.Tensor, name: str):
+    if not t.is_cuda:
+        raise QnError(f"{name} must live on the HIP device")
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise QnError(f"{name} must have shape (m, n) with unit stride along n")
+    if t.dtype == torch.float32:
+        dt = QN_F32
+    elif t.dtype == torch.bfloat16:
+        dt = QN_BF16
+    else:
+        raise QnError(f"{name}: unsupported dtype {t.dtype}")
+    m, n = t.shape
+    ld = t.stride(0) if m > 1 else max(n, 1)
+    return dt, m, n, ld
+
+
+def _dev_out(t, shape, dtype, device, name):
+    if t is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    if t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous() \
+            or t.device != device:
+        raise QnError(f"{name}: expected a contiguous {dtype} tensor of shape {shape}")
+    return t
+
+
+def qn_init():
+    _check(_lib.load().qn_init(), "qn_init")
+
+
+def qn_update(thetas, grads, tau, lam, theta_new=None, j_out=None, stream=None):
+    """theta_new (n fp32) and j_out (1 int32, on device) for the whole step."""
+    L = _lib.load()
+    dt, m, n, ld = _worker(thetas, "thetas")
+    dg, mg, ng, ldg = _worker(grads, "grads")
+    if (dt, m, n, ld) != (dg, mg, ng, ldg):
+        raise QnError("thetas and grads must agree in dtype, shape and stride")
+    theta_new = _dev_out(theta_new, (n,), torch.float32, thetas.device, "theta_new")
+    j_out = _dev_out(j_out, (1,), torch.int32, thetas.device, "j_out")
+    _check(L.qn_update_ex(thetas.data_ptr(), grads.data_ptr(), dt, n, m, ld,
+                          float(tau), float(lam), theta_new.data_ptr(),
+                          j_out.data_ptr(), _stream(stream)), "qn_update")
+    return theta_new, j_out
+
+
+def qn_gram(grads, C=None, w=None, stream=None):
+    """C = G^T G (m, m) and w = G^T g_bar (m,), float64 on device."""
+    L = _lib.load()
+    dt, m, n, ld = _worker(grads, "grads")
+    C = _dev_out(C, (m, m), torch.float64, grads.device, "C")
+    w = _dev_out(w, (m,), torch.float64, grads.device, "w")
+    _check(L.qn_gram_ex(grads.data_ptr(), dt, n, m, ld, C.data_ptr(),
+                        w.data_ptr(), _stream(stream)), "qn_gram")
+    return C, w
+
+
+def qn_eig(C, w, lam, stream=None):
+    """Returns (sigma (m,), V (m, m) with V[k] = v_k, c (m,) fp32, j (1,) int32)."""
+    L = _lib.load()
+    if not (C.is_cuda and w.is_cuda and C.dtype == torch.float64 and
+            w.dtype == torch.float64 and C.is_contiguous() and w.is_contiguous()
+            and C.dim() == 2 and C.shape[0] == C.shape[1] == w.shape[0]):
+        raise QnError("C must be (m, m) and w (m,), contiguous float64 on device")
+    m = C.shape[0]
+    dev = C.device
+    sigma = torch.empty(m, dtype=torch.float64, device=dev)
+    V = torch.empty((m, m), dtype=torch.float64, device=dev)
+    c = torch.empty(m, dtype=torch.float32, device=dev)
+    j = torch.empty(1, dtype=torch.int32, device=dev)
+    _check(L.qn_eig(C.data_ptr(), w.data_ptr(), m, float(lam), sigma.data_ptr(),
+                    V.data_ptr(), c.data_ptr(), j.data_ptr(), _stream(stream)),
+           "qn_eig")
+    return sigma, V, c, j
+
+
+def qn_apply(thetas, grads, c, tau, theta_new=None, stream=None):
+    L = _lib.load()
+    dt, m, n, ld = _worker(thetas, "thetas")
+    dg, mg, ng, ldg = _worker(grads, "grads")
+    if (dt, m, n, ld) != (dg, mg, ng, ldg):
+        raise QnError("thetas and grads must agree in dtype, shape and stride")
+    if not (c.is_cuda and c.dtype == torch.float32 and c.is_contiguous()
+            and tuple(c.shape) == (m,)):
+        raise QnError("c must be a contiguous float32 tensor of shape (m,) on device")
+    theta_new = _dev_out(theta_new, (n,), torch.float32, thetas.device, "theta_new")
+    _check(L.qn_apply_ex(thetas.data_ptr(), grads.data_ptr(), dt, n, m, ld,
+                         c.data_ptr(), float(tau), theta_new.data_ptr(),
+                         _stream(stream)), "qn_apply")
+    return theta_new
+
+
+def trace_begin(max_launches: int = 4096):
+    _check(_lib.load().qn_trace_begin(int(max_launches)), "qn_trace_begin")
+
+
+def trace_end():
+    """Returns {kernel name: (summed ms, launches)}."""
+    ms = (ctypes.c_double * len(KERNEL_NAMES))()
+    cnt = (ctypes.c_int * len(KERNEL_NAMES))()
+    _check(_lib.load().qn_trace_end(ms, cnt), "qn_trace_end")
+    return {name: (ms[i], cnt[i]) for i, name in enumerate(KERNEL_NAMES)}
