@@ -114,7 +114,7 @@ def _engineered_C(m, svals, seed):
     W = Q[:, 1:]
     s = np.asarray(svals, float)
     C = (W * s ** 2) @ W.T
-    w = W @ rng.standard_normal(m - 1) * s
+    w = W @ (rng.standard_normal(m - 1) * s)
     return C, w
 
 
