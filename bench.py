@@ -55,8 +55,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2_small")
     ap.add_argument("--n", type=int, default=0, help="override the row count")
-    ap.add_argument("--cpu-sample-rows", type=int, default=12_000_000)
+    ap.add_argument("--cpu-sample-rows", type=int, default=40_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 4 GiB device copy (a kernel of "
+                         "known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no "
@@ -88,6 +91,14 @@ def main():
     for _ in range(args.warmup):
         qn.qn_update(thetas, grads, wl.tau, wl.lam, theta_new, j_out)
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        qn.probe_copy(src, dst)       # reads 4 GiB, writes 4 GiB
+        qn.probe_read(src)            # reads 4 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     qn.trace_begin(args.steps * len(qn.KERNEL_NAMES) + 8)
     torch.cuda.synchronize()

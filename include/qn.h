@@ -169,6 +169,18 @@ int qn_trace_end(double *ms_sum /* host */, int *launches /* host */);
 /* host: static name of a kernel id */
 const char *qn_kernel_name(int kernel_id);
 
+/* ---- bandwidth probes (diagnostics; not part of the method) ----------------
+ * Kernels of exactly known HBM traffic.  They calibrate hardware byte counters
+ * and measure the streaming ceiling that the Gram and apply passes are compared
+ * with.  bytes must be a positive multiple of 16, pointers 16-byte aligned.
+ * qn_probe_copy : dst[0..bytes) = src[0..bytes); reads bytes, writes bytes.
+ * qn_probe_read : reads src[0..bytes) and writes qn_probe_sink_floats() floats
+ *                 of no meaning to sink (the caller sizes sink with that call;
+ *                 it returns -1 when no gfx950 device is current). */
+int qn_probe_copy(const void *src, void *dst, int64_t bytes, qn_stream_t stream);
+int qn_probe_read(const void *src, int64_t bytes, float *sink, qn_stream_t stream);
+int qn_probe_sink_floats(void);
+
 #ifdef __cplusplus
 }
 #endif

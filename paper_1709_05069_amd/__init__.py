@@ -9,4 +9,5 @@ when the HIP library has not been built.
 """
 from . import synth  # noqa: F401
 from .qn import (qn_update, qn_gram, qn_eig, qn_apply, qn_init,  # noqa: F401
-                 trace_begin, trace_end, KERNEL_NAMES, QnError)
+                 trace_begin, trace_end, probe_copy, probe_read,
+                 KERNEL_NAMES, QnError)

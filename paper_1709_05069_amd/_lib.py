@@ -28,6 +28,9 @@ SIGNATURES = {
     "qn_gram_ex": (_int, [_vp, _int, _i64, _int, _i64, _vp, _vp, _vp]),
     "qn_apply_ex": (_int, [_vp, _vp, _int, _i64, _int, _i64, _vp, _f32, _vp,
                            _vp]),
+    "qn_probe_copy": (_int, [_vp, _vp, _i64, _vp]),
+    "qn_probe_read": (_int, [_vp, _i64, _vp, _vp]),
+    "qn_probe_sink_floats": (_int, []),
     "qn_trace_begin": (_int, [_int]),
     "qn_trace_end": (_int, [_vp, _vp]),
 }

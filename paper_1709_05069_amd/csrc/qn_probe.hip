@@ -1,0 +1,89 @@
+// Bandwidth probes: a plain 128-bit grid-stride copy and a read-only sum.
+// They move a known number of bytes, so they calibrate hardware byte counters
+// and give the streaming ceiling the Gram and apply passes are compared with.
+#include "qn_internal.h"
+
+namespace qn {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+constexpr int kProbeThreads = 256;
+
+__global__ __launch_bounds__(kProbeThreads) void probe_copy(
+    const v4f *__restrict__ src, v4f *__restrict__ dst, int64_t nvec)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kProbeThreads;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kProbeThreads + threadIdx.x;
+         i < nvec; i += stride)
+        dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(kProbeThreads) void probe_read(
+    const v4f *__restrict__ src, int64_t nvec, float *__restrict__ sink)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kProbeThreads;
+    v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    int64_t i = static_cast<int64_t>(blockIdx.x) * kProbeThreads + threadIdx.x;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+        const v4f a = src[i], b = src[i + stride], c = src[i + 2 * stride],
+                  d = src[i + 3 * stride];
+        acc += (a + b) + (c + d);
+    }
+    for (; i < nvec; i += stride)
+        acc += src[i];
+    // one store per thread keeps the loads alive; the value is not meaningful
+    sink[static_cast<int64_t>(blockIdx.x) * kProbeThreads + threadIdx.x] =
+        (acc.x + acc.y) + (acc.z + acc.w);
+}
+
+}  // namespace qn
+
+using namespace qn;
+
+extern "C" {
+
+int qn_probe_copy(const void *src, void *dst, int64_t bytes, qn_stream_t stream)
+{
+    if (!src || !dst || bytes < 16 || bytes % 16 != 0 ||
+        reinterpret_cast<uintptr_t>(src) % 16 != 0 ||
+        reinterpret_cast<uintptr_t>(dst) % 16 != 0)
+        return QN_EINVAL;
+    Workspace *ws = nullptr;
+    const int rc = get_workspace(&ws);
+    if (rc != QN_OK)
+        return rc;
+    const int64_t nvec = bytes / 16;
+    int64_t want = (nvec + kProbeThreads - 1) / kProbeThreads;
+    const int64_t cap = static_cast<int64_t>(ws->cu_count) * 8;
+    const int grid = static_cast<int>(want < cap ? want : cap);
+    hipLaunchKernelGGL(probe_copy, dim3(grid), dim3(kProbeThreads), 0,
+                       static_cast<hipStream_t>(stream),
+                       static_cast<const v4f *>(src), static_cast<v4f *>(dst), nvec);
+    return check_launch();
+}
+
+int qn_probe_read(const void *src, int64_t bytes, float *sink, qn_stream_t stream)
+{
+    if (!src || !sink || bytes < 16 || bytes % 16 != 0 ||
+        reinterpret_cast<uintptr_t>(src) % 16 != 0)
+        return QN_EINVAL;
+    Workspace *ws = nullptr;
+    const int rc = get_workspace(&ws);
+    if (rc != QN_OK)
+        return rc;
+    const int64_t nvec = bytes / 16;
+    const int grid = ws->cu_count * 8;   // sink must hold grid*256 floats
+    hipLaunchKernelGGL(probe_read, dim3(grid), dim3(kProbeThreads), 0,
+                       static_cast<hipStream_t>(stream),
+                       static_cast<const v4f *>(src), nvec, sink);
+    return check_launch();
+}
+
+int qn_probe_sink_floats(void)
+{
+    Workspace *ws = nullptr;
+    if (get_workspace(&ws) != QN_OK)
+        return -1;
+    return ws->cu_count * 8 * kProbeThreads;
+}
+
+}  // extern "C"

@@ -121,6 +121,27 @@ def qn_apply(thetas, grads, c, tau, theta_new=None, stream=None):
     return theta_new
 
 
+def probe_copy(src, dst, stream=None):
+    """dst = src through the library's plain copy kernel (known traffic)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise QnError("probe_copy: size mismatch")
+    _check(_lib.load().qn_probe_copy(src.data_ptr(), dst.data_ptr(), nbytes,
+                                     _stream(stream)), "qn_probe_copy")
+
+
+def probe_read(src, stream=None):
+    """Streams src once through the library's read-only kernel."""
+    L = _lib.load()
+    nsink = L.qn_probe_sink_floats()
+    if nsink < 0:
+        raise QnError("probe_read: no gfx950 device")
+    sink = torch.empty(nsink, dtype=torch.float32, device=src.device)
+    _check(L.qn_probe_read(src.data_ptr(), src.numel() * src.element_size(),
+                           sink.data_ptr(), _stream(stream)), "qn_probe_read")
+    return sink
+
+
 def trace_begin(max_launches: int = 4096):
     _check(_lib.load().qn_trace_begin(int(max_launches)), "qn_trace_begin")
 

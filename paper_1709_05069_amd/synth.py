@@ -23,7 +23,7 @@ import math
 
 import torch
 
-CHUNK_ROWS = 1 << 22
+CHUNK_ROWS = 1 << 24
 
 
 @dataclass(frozen=True)
