@@ -2,19 +2,26 @@
 // (Section 2: Sigma_G / V_G, the rule after eq. (3), alpha_k of eq. (4)).
 //
 // One workgroup, everything in LDS, fp64 throughout.  The solver is the
-// parallel-order two-sided Jacobi method: the m indices are paired by a
-// round-robin tournament (m/2 disjoint pairs per round, m-1 rounds per sweep);
-// in each round the m/2 plane rotations are computed first, then every 2x2
-// block of the matrix (pair x pair) is updated as J_a^T B J_b by one thread, and
-// the eigenvector matrix is updated as V J.  Odd m is padded with an inert zero
-// row/column.
+// parallel-order two-sided Jacobi method.  The matrix is padded to M = 2, 4, 8,
+// 16 or 32 (inert zero rows/columns).  The M indices are paired by a
+// round-robin tournament: M/2 disjoint pairs per round, M-1 rounds per sweep,
+// the schedule tabulated once in LDS.  One round costs one barrier:
+//   * every wavefront computes all M/2 plane rotations redundantly (lane l owns
+//     pair l mod M/2) from the current matrix, so no cross-wave exchange of the
+//     rotations is needed; a thread fetches the two it needs by lane shuffle;
+//   * thread (a, b) rewrites the 2x2 block (pair a) x (pair b) as J_a^T B J_b,
+//     reading the current copy of the matrix and writing the other copy
+//     (double buffering removes the read/write hazard inside a round);
+//   * the same thread applies J_a to two rows of the eigenvector matrix.
+// Reciprocals and reciprocal square roots come from the hardware estimates
+// refined by Newton steps to full double precision; the matrix is pre-scaled by
+// a power of two so that squares cannot overflow or vanish.
 #include "qn_internal.h"
 
 namespace qn {
 
 constexpr int kEigThreads = 256;
 constexpr int kEigMaxSweeps = 30;
-constexpr int kLd = QN_MAX_M + 1;   // padded leading dimension in LDS
 
 __device__ __forceinline__ double block_sum(double v, double *scratch)
 {
@@ -31,36 +38,98 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
     return r;
 }
 
+__device__ __forceinline__ double block_max(double v, double *scratch)
+{
+    scratch[threadIdx.x] = v;
+    __syncthreads();
+    for (int s = kEigThreads / 2; s > 0; s >>= 1) {
+        if (threadIdx.x < s)
+            scratch[threadIdx.x] = fmax(scratch[threadIdx.x], scratch[threadIdx.x + s]);
+        __syncthreads();
+    }
+    const double r = scratch[0];
+    __syncthreads();
+    return r;
+}
+
+// 1/x and 1/sqrt(x) to double precision: hardware estimate + Newton steps.
+__device__ __forceinline__ double fast_rcp(double x)
+{
+    double r = __builtin_amdgcn_rcp(x);
+    r = fma(fma(-x, r, 1.0), r, r);
+    r = fma(fma(-x, r, 1.0), r, r);
+    return r;
+}
+
+__device__ __forceinline__ double fast_rsqrt(double x)
+{
+    double r = __builtin_amdgcn_rsq(x);
+    // r <- r + r*(1 - x r^2)/2, three times
+    double e = fma(-x * r, r, 1.0);
+    r = fma(0.5 * r, e, r);
+    e = fma(-x * r, r, 1.0);
+    r = fma(0.5 * r, e, r);
+    e = fma(-x * r, r, 1.0);
+    r = fma(0.5 * r, e, r);
+    return r;
+}
+
+// Plane rotation J = [[c, s], [-s, c]] that annihilates the (p, q) entry of a
+// symmetric matrix: t = tan(theta) is the smaller root of t^2 + 2 zeta t - 1
+// with zeta = (aqq - app) / (2 apq).
+__device__ __forceinline__ void rotation(double app, double aqq, double apq,
+                                         double &c, double &s)
+{
+    c = 1.0;
+    s = 0.0;
+    if (apq != 0.0) {
+        const double delta = aqq - app, twice = 2.0 * apq;
+        const double h2 = fma(delta, delta, twice * twice);
+        if (!(h2 > 1e-290))      // both far below the scaled matrix norm
+            return;
+        const double hyp = h2 * fast_rsqrt(h2);                  // sqrt(h2)
+        const double den = delta + copysign(hyp, delta);
+        const double t = twice * fast_rcp(den);
+        c = fast_rsqrt(fma(t, t, 1.0));
+        s = t * c;
+    }
+}
+
+template <int M>
 __global__ __launch_bounds__(kEigThreads) void eig_select(
     const double *__restrict__ C, const double *__restrict__ w, int m,
     double lambda, double *__restrict__ sigma_out, double *__restrict__ V_out,
     float *__restrict__ c_out, int *__restrict__ j_out)
 {
-    __shared__ double A[QN_MAX_M][kLd];
-    __shared__ double V[QN_MAX_M][kLd];      // V[k][r]: component r of column k
+    constexpr int NP = M / 2;          // pairs per round
+    constexpr int ROUNDS = M - 1;
+    constexpr int LD = M + 1;          // padded leading dimension in LDS
+    __shared__ double A[2][M][LD];
+    __shared__ double V[M][LD];        // V[k][r]: component r of column k
     __shared__ double scratch[kEigThreads];
-    __shared__ double cs[QN_MAX_M / 2], sn[QN_MAX_M / 2];
-    __shared__ int pp[QN_MAX_M / 2], qq[QN_MAX_M / 2];
-    __shared__ double wv[QN_MAX_M], sig[QN_MAX_M], coef[QN_MAX_M], cvec[QN_MAX_M];
-    __shared__ int perm[QN_MAX_M];
+    __shared__ unsigned char sp[ROUNDS][NP], sq[ROUNDS][NP];
+    __shared__ double wv[M], sig[M], coef[M], cvec[M];
+    __shared__ int perm[M];
     __shared__ int bad, jsel;
 
     const int tid = threadIdx.x;
-    const int M = m + (m & 1);
+    const int lane = tid & 63;
     if (tid == 0)
         bad = 0;
     __syncthreads();
 
-    // load the symmetric part; pad; V = I; non-finite scan
-    for (int e = tid; e < QN_MAX_M * QN_MAX_M; e += kEigThreads) {
-        const int k = e / QN_MAX_M, l = e % QN_MAX_M;
+    // symmetric part, zero padding, V = I, non-finite scan, schedule
+    double amax = 0.0;
+    for (int e = tid; e < M * M; e += kEigThreads) {
+        const int k = e / M, l = e % M;
         double v = 0.0;
         if (k < m && l < m) {
             v = 0.5 * (C[l * m + k] + C[k * m + l]);
             if (!isfinite(v))
                 bad = 1;
+            amax = fmax(amax, fabs(v));
         }
-        A[k][l] = v;
+        A[0][k][l] = v;
         V[k][l] = (k == l) ? 1.0 : 0.0;
     }
     if (tid < m) {
@@ -68,115 +137,113 @@ __global__ __launch_bounds__(kEigThreads) void eig_select(
         if (!isfinite(wv[tid]))
             bad = 1;
     }
+    for (int e = tid; e < ROUNDS * NP; e += kEigThreads) {
+        const int round = e / NP, i = e % NP;
+        int p, q;
+        if (i == 0) {
+            p = round;
+            q = M - 1;
+        } else {
+            p = (round + i) % (M - 1);
+            q = (round - i + (M - 1)) % (M - 1);
+        }
+        sp[round][i] = static_cast<unsigned char>(p < q ? p : q);
+        sq[round][i] = static_cast<unsigned char>(p < q ? q : p);
+    }
     __syncthreads();
 
     if (bad) {   // uniform: read after the barrier
+        const double qnan = __longlong_as_double(0x7ff8000000000000LL);
         if (tid < m) {
             c_out[tid] = 0.0f;
             if (sigma_out)
-                sigma_out[tid] = __longlong_as_double(0x7ff8000000000000LL);
+                sigma_out[tid] = qnan;
         }
         if (V_out)
             for (int e = tid; e < m * m; e += kEigThreads)
-                V_out[e] = __longlong_as_double(0x7ff8000000000000LL);
+                V_out[e] = qnan;
         if (tid == 0)
             *j_out = -1;
         return;
     }
 
+    // scale by a power of two so that the largest entry lies in [1, 2)
+    amax = block_max(amax, scratch);
+    int expo = 0;
+    if (amax > 0.0)
+        (void)frexp(amax, &expo);
+    const double scale = ldexp(1.0, 1 - expo), unscale = ldexp(1.0, expo - 1);
     double tot = 0.0;
     for (int e = tid; e < M * M; e += kEigThreads) {
-        const double v = A[e / M][e % M];
+        const double v = A[0][e / M][e % M] * scale;
+        A[0][e / M][e % M] = v;
         tot += v * v;
     }
-    const double total2 = block_sum(tot, scratch);
-    const double tol2 = 1e-28 * total2;
+    const double tol2 = 1e-28 * block_sum(tot, scratch);
 
-    const int npairs = M / 2;
+    int cur = 0;
+    const bool active = tid < NP * NP;
+    const int pa = tid / NP, pb = tid % NP;      // this thread's pair indices
     for (int sweep = 0; sweep < kEigMaxSweeps; ++sweep) {
         double off = 0.0;
         for (int e = tid; e < M * M; e += kEigThreads) {
             const int k = e / M, l = e % M;
             if (k != l)
-                off += A[k][l] * A[k][l];
+                off += A[cur][k][l] * A[cur][k][l];
         }
-        const double off2 = block_sum(off, scratch);
-        if (off2 <= tol2)
+        if (block_sum(off, scratch) <= tol2)
             break;
 
-        for (int round = 0; round < M - 1; ++round) {
-            if (tid < npairs) {
-                int p, q;
-                if (tid == 0) {
-                    p = round;
-                    q = M - 1;
-                } else {
-                    p = (round + tid) % (M - 1);
-                    q = (round - tid + (M - 1)) % (M - 1);
-                }
-                if (p > q) {
-                    const int t = p;
-                    p = q;
-                    q = t;
-                }
-                const double apq = A[p][q];
-                double c = 1.0, s = 0.0;
-                if (apq != 0.0) {
-                    const double zeta = (A[q][q] - A[p][p]) / (2.0 * apq);
-                    const double t = copysign(1.0, zeta) /
-                                     (fabs(zeta) + sqrt(zeta * zeta + 1.0));
-                    c = 1.0 / sqrt(t * t + 1.0);
-                    s = t * c;
-                }
-                pp[tid] = p;
-                qq[tid] = q;
-                cs[tid] = c;
-                sn[tid] = s;
-            }
-            __syncthreads();
-            // A <- J^T A J, one 2x2 block (pair a) x (pair b) per thread
-            for (int blk = tid; blk < npairs * npairs; blk += kEigThreads) {
-                const int a = blk / npairs, b = blk % npairs;
-                const int p1 = pp[a], q1 = qq[a], p2 = pp[b], q2 = qq[b];
-                const double c1 = cs[a], s1 = sn[a], c2 = cs[b], s2 = sn[b];
-                const double b00 = A[p1][p2], b01 = A[p1][q2];
-                const double b10 = A[q1][p2], b11 = A[q1][q2];
+        for (int round = 0; round < ROUNDS; ++round) {
+            // every wavefront: lane l computes the rotation of pair l mod NP
+            const int pr = lane % NP;
+            const int rp = sp[round][pr], rq = sq[round][pr];
+            double rc, rs;
+            rotation(A[cur][rp][rp], A[cur][rq][rq], A[cur][rp][rq], rc, rs);
+            const double c1 = __shfl(rc, pa), s1 = __shfl(rs, pa);
+            const double c2 = __shfl(rc, pb), s2 = __shfl(rs, pb);
+            if (active) {
+                const int p1 = sp[round][pa], q1 = sq[round][pa];
+                const int p2 = sp[round][pb], q2 = sq[round][pb];
+                const double b00 = A[cur][p1][p2], b01 = A[cur][p1][q2];
+                const double b10 = A[cur][q1][p2], b11 = A[cur][q1][q2];
+                // V <- V J_a on rows 2*pb, 2*pb + 1
+                const double vp0 = V[p1][2 * pb], vq0 = V[q1][2 * pb];
+                const double vp1 = V[p1][2 * pb + 1], vq1 = V[q1][2 * pb + 1];
+                // B <- J_a^T B J_b
                 const double t00 = c1 * b00 - s1 * b10, t01 = c1 * b01 - s1 * b11;
                 const double t10 = s1 * b00 + c1 * b10, t11 = s1 * b01 + c1 * b11;
                 double n00 = c2 * t00 - s2 * t01, n01 = s2 * t00 + c2 * t01;
                 double n10 = c2 * t10 - s2 * t11, n11 = s2 * t10 + c2 * t11;
-                if (a == b) {   // the annihilated pair: exactly diagonal
+                if (pa == pb) {   // the annihilated pair: exactly diagonal
                     n01 = 0.0;
                     n10 = 0.0;
                 }
-                A[p1][p2] = n00;
-                A[p1][q2] = n01;
-                A[q1][p2] = n10;
-                A[q1][q2] = n11;
-            }
-            // V <- V J
-            for (int it = tid; it < npairs * M; it += kEigThreads) {
-                const int a = it / M, r = it % M;
-                const int p = pp[a], q = qq[a];
-                const double c = cs[a], s = sn[a];
-                const double vp = V[p][r], vq = V[q][r];
-                V[p][r] = c * vp - s * vq;
-                V[q][r] = s * vp + c * vq;
+                A[cur ^ 1][p1][p2] = n00;
+                A[cur ^ 1][p1][q2] = n01;
+                A[cur ^ 1][q1][p2] = n10;
+                A[cur ^ 1][q1][q2] = n11;
+                V[p1][2 * pb] = c1 * vp0 - s1 * vq0;
+                V[q1][2 * pb] = s1 * vp0 + c1 * vq0;
+                V[p1][2 * pb + 1] = c1 * vp1 - s1 * vq1;
+                V[q1][2 * pb + 1] = s1 * vp1 + c1 * vq1;
             }
             __syncthreads();
+            cur ^= 1;
         }
     }
 
-    // sort descending by counting; sigma = sqrt(max(mu, 0))
+    // sort descending by counting; sigma = sqrt(max(mu, 0)); padded indices
+    // (>= m) are never coupled to the others and are left out
     if (tid < m) {
-        const double mu = A[tid][tid];
+        const double mu = A[cur][tid][tid];
         int rank = 0;
         for (int l = 0; l < m; ++l) {
-            const double ml = A[l][l];
+            const double ml = A[cur][l][l];
             rank += (ml > mu) || (ml == mu && l < tid);
         }
         perm[rank] = tid;
-        sig[rank] = mu > 0.0 ? sqrt(mu) : 0.0;
+        sig[rank] = mu > 0.0 ? sqrt(mu * unscale) : 0.0;
     }
     __syncthreads();
 
@@ -237,8 +304,16 @@ int launch_eig(const double *C, const double *w, int m, float lambda,
                hipStream_t stream)
 {
     TraceScope ts(QN_K_EIG, stream);
-    hipLaunchKernelGGL(eig_select, dim3(1), dim3(kEigThreads), 0, stream, C, w, m,
-                       static_cast<double>(lambda), sigma, V, c, j_out);
+    const double lam = static_cast<double>(lambda);
+#define QN_EIG_LAUNCH(MM)                                                            \
+    hipLaunchKernelGGL(eig_select<MM>, dim3(1), dim3(kEigThreads), 0, stream, C, w, \
+                       m, lam, sigma, V, c, j_out)
+    if (m <= 2) QN_EIG_LAUNCH(2);
+    else if (m <= 4) QN_EIG_LAUNCH(4);
+    else if (m <= 8) QN_EIG_LAUNCH(8);
+    else if (m <= 16) QN_EIG_LAUNCH(16);
+    else QN_EIG_LAUNCH(32);
+#undef QN_EIG_LAUNCH
     return check_launch();
 }
 
