@@ -20,6 +20,15 @@ METRIC = ("quasi-Newton updates/sec and achieved HBM GB/s (% of peak) "
           "at n=124M, m=32")
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by the same counters on a 4 GiB qn_probe_copy) for the kernels as
+# committed; see profiles/qn_update_gpt2_small_hbm_counters.md.  Keyed by
+# (workload, n, kernel); anything else reports null.
+MEASURED_TRAFFIC = {
+    ("gpt2_small", 124_000_000, "apply_kernel"): 31.7442e9 + 0.4960e9,
+    ("gpt2_small", 124_000_000, "gram_stage1"): 15.8724e9 + 0.0031e9,
+}
+
 
 def algorithmic_bytes(n, m, esz):
     """Bytes each streaming kernel must move per launch: the Gram pass reads
@@ -130,10 +139,7 @@ def main():
         "kernel": dominant, "bound": "hbm",
         "achieved": dk.get("achieved_GBps"), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": dk.get("frac_of_peak"),
-        # HBM bytes per launch from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
-        # are recorded in profiles/; null here until taken for this build of
-        # the kernel
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC.get((args.workload, wl.n, dominant)),
     }
     total_bytes = sum(abytes.values())
     whole = {
