@@ -25,7 +25,7 @@ HBM_PEAK_GBS = 8000.0
 # committed; see profiles/qn_update_gpt2_small_hbm_counters.md.  Keyed by
 # (workload, n, kernel); anything else reports null.
 MEASURED_TRAFFIC = {
-    ("gpt2_small", 124_000_000, "apply_kernel"): 31.7442e9 + 0.4960e9,
+    ("gpt2_small", 124_000_000, "apply_kernel"): 31.7441e9 + 0.4960e9,
     ("gpt2_small", 124_000_000, "gram_stage1"): 15.8724e9 + 0.0031e9,
 }
 

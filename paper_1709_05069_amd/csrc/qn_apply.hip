@@ -25,7 +25,13 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 
 constexpr int kApplyThreads = 256;
-constexpr int kApplyChunk = 8;     // worker columns whose loads are issued together
+// worker columns whose loads are issued together (two such chunks are in flight)
+#ifndef QN_APPLY_CHUNK_F32
+#define QN_APPLY_CHUNK_F32 8
+#endif
+template <int DT> struct ApplyChunk {
+    static constexpr int value = DT == QN_F32 ? QN_APPLY_CHUNK_F32 : QN_APPLY_CHUNK_F32 / 2;
+};
 
 template <int DT, int R>
 __device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (&x)[R])
@@ -56,15 +62,16 @@ __device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (
     }
 }
 
-// Processes rows [row, row + R) of every worker column.
+// theta_new for rows [row, row + R), from every worker column.
 template <int DT, int MC, int R>
-__device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
-                                           const void *__restrict__ grads,
-                                           int64_t row, int m_rt, int64_t ld,
-                                           const float *__restrict__ c,
-                                           float csum, float tau, float inv_m,
-                                           float *__restrict__ out)
+__device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
+                                             const void *__restrict__ grads,
+                                             int64_t row, int m_rt, int64_t ld,
+                                             const float *__restrict__ c,
+                                             float csum, float tau, float inv_m,
+                                             float (&res)[R])
 {
+    constexpr int kApplyChunk = ApplyChunk<DT>::value;
     const int m = MC ? MC : m_rt;
     float p[R], r[R], st[R], sh[R], acc[R];
     load_vec<DT, R>(thetas, row, p);
@@ -75,16 +82,26 @@ __device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
         sh[e] = 0.0f;
         acc[e] = 0.0f;
     }
+    // Columns 1..m-1 in chunks of kApplyChunk, software-pipelined over a real
+    // (not unrolled) loop: the loads of the next chunk are issued before the
+    // current chunk is consumed, so 2*kApplyChunk 128-bit loads per lane stay in
+    // flight while the register footprint stays bounded.
+    float th[kApplyChunk][R], gr[kApplyChunk][R];
 #pragma unroll
-    for (int k0 = 1; k0 < (MC ? MC : QN_MAX_M); k0 += kApplyChunk) {
-        if (k0 >= m)
-            break;
-        float th[kApplyChunk][R], gr[kApplyChunk][R];
+    for (int u = 0; u < kApplyChunk; ++u)
+        if (1 + u < m) {
+            load_vec<DT, R>(thetas, (1 + u) * ld + row, th[u]);
+            load_vec<DT, R>(grads, (1 + u) * ld + row, gr[u]);
+        }
+#pragma unroll 1
+    for (int k0 = 1; k0 < m; k0 += kApplyChunk) {
+        float thn[kApplyChunk][R], grn[kApplyChunk][R];
+        const int kn = k0 + kApplyChunk;
 #pragma unroll
         for (int u = 0; u < kApplyChunk; ++u)
-            if (k0 + u < m) {
-                load_vec<DT, R>(thetas, (k0 + u) * ld + row, th[u]);
-                load_vec<DT, R>(grads, (k0 + u) * ld + row, gr[u]);
+            if (kn + u < m) {
+                load_vec<DT, R>(thetas, (kn + u) * ld + row, thn[u]);
+                load_vec<DT, R>(grads, (kn + u) * ld + row, grn[u]);
             }
 #pragma unroll
         for (int u = 0; u < kApplyChunk; ++u)
@@ -99,14 +116,33 @@ __device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
                     acc[e] = fmaf(ck, t - h, acc[e]);
                 }
             }
+#pragma unroll
+        for (int u = 0; u < kApplyChunk; ++u)
+#pragma unroll
+            for (int e = 0; e < R; ++e) {
+                th[u][e] = thn[u][e];
+                gr[u][e] = grn[u][e];
+            }
     }
-    float res[R];
 #pragma unroll
     for (int e = 0; e < R; ++e) {
         const float mt = st[e] * inv_m, mh = sh[e] * inv_m;
         const float corr = acc[e] - csum * (mt - mh);
         res[e] = (p[e] + mt) - tau * ((r[e] + mh) + corr);
     }
+}
+
+// Computes rows [row, row + R) and stores them straight to memory.
+template <int DT, int MC, int R>
+__device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
+                                           const void *__restrict__ grads,
+                                           int64_t row, int m_rt, int64_t ld,
+                                           const float *__restrict__ c,
+                                           float csum, float tau, float inv_m,
+                                           float *__restrict__ out)
+{
+    float res[R];
+    compute_rows<DT, MC, R>(thetas, grads, row, m_rt, ld, c, csum, tau, inv_m, res);
     if constexpr (R == 1) {
         out[row] = res[0];
     } else {
@@ -145,11 +181,88 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
     }
 }
 
+// Large-n variant.  A thin write stream mixed into a read stream that saturates
+// HBM is disproportionately expensive (measured on MI355X: the 0.5 GB of output
+// at the 124M x 32 size costs 0.9 ms when every wave stores its 1 KiB as soon as
+// it is computed, 0.26 ms when each CU writes 128 KiB bursts).  So one block
+// per CU keeps a slab of results in LDS and writes it out in one contiguous
+// burst.  Same arithmetic, same bits as apply_kernel.
+#ifndef QN_STAGED_THREADS
+#define QN_STAGED_THREADS 256
+#endif
+constexpr int kStagedThreads = QN_STAGED_THREADS;
+#ifndef QN_STAGED_LDS_KB
+#define QN_STAGED_LDS_KB 128
+#endif
+constexpr int kStagedLdsBytes = QN_STAGED_LDS_KB * 1024;
+
+template <int DT, int MC>
+__global__ __launch_bounds__(kStagedThreads) void apply_staged(
+    const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
+    int m_rt, int64_t ld, const float *__restrict__ c, float tau,
+    float *__restrict__ out)
+{
+    constexpr int R = DT == QN_F32 ? 4 : 8;        // rows per lane per step
+    constexpr int Q = R / 4;                       // 128-bit results per lane per step
+    constexpr int STEPS = kStagedLdsBytes / (kStagedThreads * 16 * Q);
+    extern __shared__ v4f stage[];
+    const int m = MC ? MC : m_rt;
+    float csum = 0.0f;
+    for (int k = 0; k < m; ++k)
+        csum += c[k];
+    const float inv_m = 1.0f / static_cast<float>(m);
+
+    const int64_t nvec = n / R;
+    const int64_t slab = static_cast<int64_t>(STEPS) * kStagedThreads;   // lane-steps per slab
+#pragma unroll 1
+    for (int64_t base = static_cast<int64_t>(blockIdx.x) * slab; base < nvec;
+         base += static_cast<int64_t>(gridDim.x) * slab) {
+#pragma unroll 1
+        for (int it = 0; it < STEPS; ++it) {
+            const int64_t v = base + static_cast<int64_t>(it) * kStagedThreads + threadIdx.x;
+            if (v < nvec) {
+                float res[R];
+                compute_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, csum, tau, inv_m, res);
+#pragma unroll
+                for (int h = 0; h < Q; ++h)
+                    stage[(it * kStagedThreads + threadIdx.x) * Q + h] =
+                        (v4f){res[4 * h], res[4 * h + 1], res[4 * h + 2], res[4 * h + 3]};
+            }
+        }
+        __syncthreads();
+        // the slab's results are contiguous in memory: rows [base*R, (base+slab)*R)
+        v4f *dst = reinterpret_cast<v4f *>(out) + base * Q;
+        const int64_t left = (nvec - base) * Q;
+        const int count = static_cast<int>(left < slab * Q ? left : slab * Q);
+#pragma unroll 1
+        for (int i = threadIdx.x; i < count; i += kStagedThreads)
+            __builtin_nontemporal_store(stage[i], dst + i);
+        __syncthreads();
+    }
+
+    const int64_t tail0 = nvec * R;                // rows past the last full vector
+    if (blockIdx.x == 0 && tail0 + threadIdx.x < n)
+        apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c, csum,
+                              tau, inv_m, out);
+}
+
 template <int DT, int MC>
 static void launch_mc(bool vec, int grid, const void *thetas, const void *grads,
                       int64_t n, int m, int64_t ld, const float *c, float tau,
                       float *out, hipStream_t stream)
 {
+    if (grid < 0) {   // staged variant, -grid blocks
+        static bool attr_set = false;   // per instantiation
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(apply_staged<DT, MC>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      kStagedLdsBytes);
+            attr_set = true;
+        }
+        hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(-grid), dim3(kStagedThreads),
+                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, tau, out);
+        return;
+    }
     if (vec)
         hipLaunchKernelGGL((apply_kernel<DT, MC, true>), dim3(grid), dim3(kApplyThreads),
                            0, stream, thetas, grads, n, m, ld, c, tau, out);
@@ -185,7 +298,12 @@ int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
     const int64_t per_block = static_cast<int64_t>(kApplyThreads) * rows_per_thread;
     int64_t want = (n + per_block - 1) / per_block;
     const int64_t cap = static_cast<int64_t>(cu_count) * 8;
-    const int grid = static_cast<int>(want < cap ? want : cap);
+    int grid = static_cast<int>(want < cap ? want : cap);
+    // large aligned problems: one block per CU with LDS-staged output bursts
+    // (each slab covers 32768 rows; worth it once every CU gets several slabs)
+    const int64_t slab_rows = kStagedLdsBytes / 4;
+    if (vec && n >= slab_rows * cu_count * 4)
+        grid = -cu_count;
 
     TraceScope ts(QN_K_APPLY, stream);
     if (dtype == QN_F32)
