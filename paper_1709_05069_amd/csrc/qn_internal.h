@@ -14,7 +14,10 @@ namespace qn {
 // (n, m, dtype).  Each block writes one partial; the partial holds the raw
 // MFMA accumulator layout: TILE_ENTRIES values per 16x16 tile, up to 3 tiles
 // (the lower triangle of a 2x2 tiling of a 32x32 matrix).
-constexpr int kGramThreads = 512;               // 8 wavefronts
+#ifndef QN_GRAM_THREADS
+#define QN_GRAM_THREADS 512                     // 8 wavefronts
+#endif
+constexpr int kGramThreads = QN_GRAM_THREADS;
 constexpr int kGramWaves = kGramThreads / 64;
 constexpr int kGramMaxBlocks = 2048;
 constexpr int kTileEntries = 256;               // 16 x 16

@@ -1,0 +1,87 @@
+"""GPU tests of the library's plumbing: streams, tracing, probes, workspace
+lifetime and the binding's argument checks."""
+import numpy as np
+import pytest
+import torch
+
+import paper_1709_05069_amd as qn
+from paper_1709_05069_amd import synth, _lib
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _inputs(n=70_000, name="gpt2_small"):
+    wl = synth.WORKLOADS[name].scaled(n)
+    th, gr = synth.make_worker_states(wl, DEV)
+    return wl, th, gr
+
+
+def test_trace_counts_every_kernel_once_per_update():
+    wl, th, gr = _inputs()
+    qn.trace_begin(64)
+    for _ in range(3):
+        qn.qn_update(th, gr, wl.tau, wl.lam)
+    tr = qn.trace_end()
+    assert set(tr) == set(qn.KERNEL_NAMES)
+    for name, (ms, cnt) in tr.items():
+        assert cnt == 3 and ms > 0.0
+    with pytest.raises(qn.QnError):
+        qn.trace_end()                       # not tracing any more
+    # more launches than slots: the surplus is simply not timed
+    qn.trace_begin(2)
+    qn.qn_update(th, gr, wl.tau, wl.lam)
+    tr = qn.trace_end()
+    assert sum(c for _, c in tr.values()) == 2
+
+
+def test_side_stream_gives_the_same_bits():
+    wl, th, gr = _inputs()
+    a, ja = qn.qn_update(th, gr, wl.tau, wl.lam)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        b, jb = qn.qn_update(th, gr, wl.tau, wl.lam)
+    s.synchronize()
+    assert torch.equal(a, b) and int(ja.item()) == int(jb.item())
+
+
+def test_probes_move_the_bytes_they_claim():
+    src = torch.randn(1 << 20, device=DEV)
+    dst = torch.zeros_like(src)
+    qn.probe_copy(src, dst)
+    sink = qn.probe_read(src)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    assert sink.numel() == _lib.load().qn_probe_sink_floats()
+    with pytest.raises(qn.QnError):
+        qn.probe_copy(src[:1001], dst[:1001])          # not a multiple of 16 bytes
+
+
+def test_shutdown_then_reuse():
+    wl, th, gr = _inputs(30_000, "resnet50")
+    a, _ = qn.qn_update(th, gr, wl.tau, wl.lam)
+    torch.cuda.synchronize()
+    assert _lib.load().qn_shutdown() == 0
+    b, _ = qn.qn_update(th, gr, wl.tau, wl.lam)          # allocates the workspace again
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_binding_rejects_bad_tensors():
+    wl, th, gr = _inputs(5_000, "small_mlp")
+    with pytest.raises(qn.QnError):
+        qn.qn_update(th.cpu(), gr.cpu(), 1.0, 0.1)
+    with pytest.raises(qn.QnError):
+        qn.qn_update(th, gr[:, :-1], 1.0, 0.1)
+    with pytest.raises(qn.QnError):
+        qn.qn_update(th.double(), gr.double(), 1.0, 0.1)
+    with pytest.raises(qn.QnError):
+        qn.qn_update(th.t(), gr.t(), 1.0, 0.1)           # rows not contiguous
+    with pytest.raises(qn.QnError):
+        qn.qn_update(th, gr, 1.0, -0.5)                  # lambda <= 0: library says EINVAL
+    with pytest.raises(qn.QnError):
+        qn.qn_apply(th, gr, torch.zeros(3, device=DEV), 1.0)
+    big = torch.zeros((33, 64), device=DEV)
+    with pytest.raises(qn.QnError):
+        qn.qn_gram(big)                                  # m > QN_MAX_M
