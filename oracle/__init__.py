@@ -27,43 +27,48 @@ _dbl = ctypes.c_double
 _vp = ctypes.c_void_p
 
 
+def load_library(path):
+    """Opens an oracle shared library and declares its signatures."""
+    L = ctypes.CDLL(path)
+    L.qno_row_means.argtypes = [_vp, _int, _i64, _int, _i64, _vp]
+    L.qno_row_means.restype = None
+    L.qno_centre.argtypes = [_vp, _int, _i64, _int, _i64, _vp, _vp]
+    L.qno_centre.restype = None
+    L.qno_gram.argtypes = [_vp, _i64, _int, _vp]
+    L.qno_gram.restype = None
+    L.qno_gemv_t.argtypes = [_vp, _i64, _int, _vp, _vp]
+    L.qno_gemv_t.restype = None
+    L.qno_jacobi_eigh.argtypes = [_vp, _int, _vp, _vp]
+    L.qno_jacobi_eigh.restype = _int
+    L.qno_sigma_from_mu.argtypes = [_vp, _int, _vp]
+    L.qno_sigma_from_mu.restype = None
+    L.qno_select_j.argtypes = [_vp, _int, _dbl]
+    L.qno_select_j.restype = _int
+    L.qno_apply_Hinv_literal.argtypes = [_vp, _vp, _i64, _int, _vp, _vp,
+                                         _int, _vp, _vp]
+    L.qno_apply_Hinv_literal.restype = None
+    L.qno_update_literal.argtypes = [_vp, _vp, _int, _i64, _int, _i64,
+                                     _dbl, _dbl, _vp, _vp, _vp, _vp, _vp,
+                                     _vp]
+    L.qno_update_literal.restype = _int
+    L.qno_gram_accumulate.argtypes = [_vp, _int, _i64, _int, _i64, _vp,
+                                      _vp]
+    L.qno_gram_accumulate.restype = None
+    L.qno_coefficients.argtypes = [_vp, _vp, _int, _dbl, _vp, _vp, _vp,
+                                   _vp, _vp]
+    L.qno_coefficients.restype = _int
+    L.qno_apply_closed_form.argtypes = [_vp, _vp, _int, _i64, _int, _i64,
+                                        _vp, _dbl, _vp]
+    L.qno_apply_closed_form.restype = None
+    return L
+
+
 def lib():
     global _LIB
     if _LIB is None:
         if not os.path.exists(_build.LIB):
             _build.build()
-        L = ctypes.CDLL(_build.LIB)
-        L.qno_row_means.argtypes = [_vp, _int, _i64, _int, _i64, _vp]
-        L.qno_row_means.restype = None
-        L.qno_centre.argtypes = [_vp, _int, _i64, _int, _i64, _vp, _vp]
-        L.qno_centre.restype = None
-        L.qno_gram.argtypes = [_vp, _i64, _int, _vp]
-        L.qno_gram.restype = None
-        L.qno_gemv_t.argtypes = [_vp, _i64, _int, _vp, _vp]
-        L.qno_gemv_t.restype = None
-        L.qno_jacobi_eigh.argtypes = [_vp, _int, _vp, _vp]
-        L.qno_jacobi_eigh.restype = _int
-        L.qno_sigma_from_mu.argtypes = [_vp, _int, _vp]
-        L.qno_sigma_from_mu.restype = None
-        L.qno_select_j.argtypes = [_vp, _int, _dbl]
-        L.qno_select_j.restype = _int
-        L.qno_apply_Hinv_literal.argtypes = [_vp, _vp, _i64, _int, _vp, _vp,
-                                             _int, _vp, _vp]
-        L.qno_apply_Hinv_literal.restype = None
-        L.qno_update_literal.argtypes = [_vp, _vp, _int, _i64, _int, _i64,
-                                         _dbl, _dbl, _vp, _vp, _vp, _vp, _vp,
-                                         _vp]
-        L.qno_update_literal.restype = _int
-        L.qno_gram_accumulate.argtypes = [_vp, _int, _i64, _int, _i64, _vp,
-                                          _vp]
-        L.qno_gram_accumulate.restype = None
-        L.qno_coefficients.argtypes = [_vp, _vp, _int, _dbl, _vp, _vp, _vp,
-                                       _vp, _vp]
-        L.qno_coefficients.restype = _int
-        L.qno_apply_closed_form.argtypes = [_vp, _vp, _int, _i64, _int, _i64,
-                                            _vp, _dbl, _vp]
-        L.qno_apply_closed_form.restype = None
-        _LIB = L
+        _LIB = load_library(_build.LIB)
     return _LIB
 
 
