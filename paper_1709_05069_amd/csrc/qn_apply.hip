@@ -29,8 +29,11 @@ constexpr int kApplyThreads = 256;
 #ifndef QN_APPLY_CHUNK_F32
 #define QN_APPLY_CHUNK_F32 8
 #endif
+#ifndef QN_APPLY_CHUNK_BF16
+#define QN_APPLY_CHUNK_BF16 2
+#endif
 template <int DT> struct ApplyChunk {
-    static constexpr int value = DT == QN_F32 ? QN_APPLY_CHUNK_F32 : QN_APPLY_CHUNK_F32 / 2;
+    static constexpr int value = DT == QN_F32 ? QN_APPLY_CHUNK_F32 : QN_APPLY_CHUNK_BF16;
 };
 
 template <int DT, int R>
@@ -187,24 +190,37 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
 // it is computed, 0.26 ms when each CU writes 128 KiB bursts).  So one block
 // per CU keeps a slab of results in LDS and writes it out in one contiguous
 // burst.  Same arithmetic, same bits as apply_kernel.
-#ifndef QN_STAGED_THREADS
-#define QN_STAGED_THREADS 256
+#ifndef QN_STAGED_THREADS_F32
+#define QN_STAGED_THREADS_F32 256
 #endif
-constexpr int kStagedThreads = QN_STAGED_THREADS;
+#ifndef QN_STAGED_THREADS_BF16
+#define QN_STAGED_THREADS_BF16 1024
+#endif
+// block size of the staged variant: fp32 streams best with few waves per CU;
+// bf16 has twice the arithmetic per byte and needs more waves to hide it
+template <int DT> struct StagedThreads {
+    static constexpr int value = DT == QN_F32 ? QN_STAGED_THREADS_F32 : QN_STAGED_THREADS_BF16;
+};
 #ifndef QN_STAGED_LDS_KB
 #define QN_STAGED_LDS_KB 128
 #endif
 constexpr int kStagedLdsBytes = QN_STAGED_LDS_KB * 1024;
 
+template <int DT> constexpr int staged_max_steps()
+{
+    return kStagedLdsBytes / (StagedThreads<DT>::value * 16 * (DT == QN_F32 ? 1 : 2));
+}
+
 template <int DT, int MC>
-__global__ __launch_bounds__(kStagedThreads) void apply_staged(
+__global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
     const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
     int m_rt, int64_t ld, const float *__restrict__ c, float tau,
-    float *__restrict__ out)
+    float *__restrict__ out, int steps)
 {
+    constexpr int kStagedThreads = StagedThreads<DT>::value;
     constexpr int R = DT == QN_F32 ? 4 : 8;        // rows per lane per step
     constexpr int Q = R / 4;                       // 128-bit results per lane per step
-    constexpr int STEPS = kStagedLdsBytes / (kStagedThreads * 16 * Q);
+    // steps <= staged_max_steps<DT>(): lane-steps per thread per slab
     extern __shared__ v4f stage[];
     const int m = MC ? MC : m_rt;
     float csum = 0.0f;
@@ -213,12 +229,12 @@ __global__ __launch_bounds__(kStagedThreads) void apply_staged(
     const float inv_m = 1.0f / static_cast<float>(m);
 
     const int64_t nvec = n / R;
-    const int64_t slab = static_cast<int64_t>(STEPS) * kStagedThreads;   // lane-steps per slab
+    const int64_t slab = static_cast<int64_t>(steps) * kStagedThreads;   // lane-steps per slab
 #pragma unroll 1
     for (int64_t base = static_cast<int64_t>(blockIdx.x) * slab; base < nvec;
          base += static_cast<int64_t>(gridDim.x) * slab) {
 #pragma unroll 1
-        for (int it = 0; it < STEPS; ++it) {
+        for (int it = 0; it < steps; ++it) {
             const int64_t v = base + static_cast<int64_t>(it) * kStagedThreads + threadIdx.x;
             if (v < nvec) {
                 float res[R];
@@ -252,6 +268,13 @@ static void launch_mc(bool vec, int grid, const void *thetas, const void *grads,
                       float *out, hipStream_t stream)
 {
     if (grid < 0) {   // staged variant, -grid blocks
+        // slab length: every block gets the same number of (nearly) full slabs
+        constexpr int R = DT == QN_F32 ? 4 : 8;
+        const int64_t per_block =
+            (n / R + static_cast<int64_t>(-grid) * StagedThreads<DT>::value - 1) /
+            (static_cast<int64_t>(-grid) * StagedThreads<DT>::value);       // lane-steps per thread
+        const int64_t rounds = (per_block + staged_max_steps<DT>() - 1) / staged_max_steps<DT>();
+        const int steps = static_cast<int>((per_block + rounds - 1) / rounds);
         static bool attr_set = false;   // per instantiation
         if (!attr_set) {
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(apply_staged<DT, MC>),
@@ -259,8 +282,8 @@ static void launch_mc(bool vec, int grid, const void *thetas, const void *grads,
                                       kStagedLdsBytes);
             attr_set = true;
         }
-        hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(-grid), dim3(kStagedThreads),
-                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, tau, out);
+        hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(-grid), dim3(StagedThreads<DT>::value),
+                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, tau, out, steps);
         return;
     }
     if (vec)
@@ -300,9 +323,9 @@ int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
     const int64_t cap = static_cast<int64_t>(cu_count) * 8;
     int grid = static_cast<int>(want < cap ? want : cap);
     // large aligned problems: one block per CU with LDS-staged output bursts
-    // (each slab covers 32768 rows; worth it once every CU gets several slabs)
+    // (a full slab covers 32768 rows; worth it once every CU gets at least one)
     const int64_t slab_rows = kStagedLdsBytes / 4;
-    if (vec && n >= slab_rows * cu_count * 4)
+    if (vec && n >= slab_rows * cu_count)
         grid = -cu_count;
 
     TraceScope ts(QN_K_APPLY, stream);
