@@ -148,6 +148,35 @@ int qn_apply_ex(const void *thetas, const void *grads, int dtype, int64_t n,
                 int m, int64_t ld, const float *c, float tau, float *theta_new,
                 qn_stream_t stream);
 
+/* ---- the operator of eq. (3)/(4) on an arbitrary vector ---------------------
+ *   out = Hinv z = z_perp + sum_{k<=j} alpha_k sigma_k^-1 y_k,  alpha_k = z^T u_k,
+ * identity on span{u_1..u_j}^perp and the secant inverse (G v_k -> Theta v_k) on
+ * the span.  Evaluated as z + (Theta - G) c_z with c_z = sum_{k<=j} v_k (v_k^T
+ * G^T z) / sigma_k^2; qn_update is this operator applied to g_bar inside eq. (2).
+ * z, out : n fp32 values (device); out must not overlap an input.
+ * Three passes over memory (Gram, G^T z, apply); j_out as for qn_update. */
+int qn_hinv(const float *thetas, const float *grads, const float *z, int64_t n, int m,
+            float lambda, float *out, int *j_out, qn_stream_t stream);
+int qn_hinv_bf16(const uint16_t *thetas, const uint16_t *grads, const float *z,
+                 int64_t n, int m, float lambda, float *out, int *j_out,
+                 qn_stream_t stream);
+int qn_hinv_ex(const void *thetas, const void *grads, int dtype, const float *z,
+               int64_t n, int m, int64_t ld, float lambda, float *out, int *j_out,
+               qn_stream_t stream);
+/* its pieces:
+ * qn_gemv_t_ex     : w = G^T z (m doubles, device) for the centred G of grads;
+ * qn_coef          : c (m floats) = sum_{k<j} v_k (v_k^T w)/sigma_k^2 from sigma, V
+ *                    as written by qn_eig and j read from device memory (*j <= 0
+ *                    gives c = 0); re-centred like qn_eig's c;
+ * qn_hinv_apply_ex : out = z + (Theta - G) c for any c. */
+int qn_gemv_t_ex(const void *grads, int dtype, const float *z, int64_t n, int m,
+                 int64_t ld, double *w, qn_stream_t stream);
+int qn_coef(const double *sigma, const double *V, const int *j, const double *w, int m,
+            float *c, qn_stream_t stream);
+int qn_hinv_apply_ex(const void *thetas, const void *grads, int dtype, const float *z,
+                     int64_t n, int m, int64_t ld, const float *c, float *out,
+                     qn_stream_t stream);
+
 /* ---- per-kernel timing (host side helper, for benchmarks) -----------------
  * Between qn_trace_begin() and qn_trace_end() every kernel the library
  * launches is bracketed by HIP events recorded on the launch stream.
@@ -162,7 +191,9 @@ enum {
     QN_K_PROJECT = 2,  /* m x m centring algebra producing C and w */
     QN_K_EIG = 3,      /* Jacobi + cutoff + coefficients */
     QN_K_APPLY = 4,    /* streaming pass over thetas and grads */
-    QN_TRACE_KERNELS = 5
+    QN_K_GEMV = 5,     /* G^T z: streaming pass over grads and z, and its reduce */
+    QN_K_COEF = 6,     /* coefficients from sigma, V, j, w */
+    QN_TRACE_KERNELS = 7
 };
 int qn_trace_begin(int max_launches);
 int qn_trace_end(double *ms_sum /* host */, int *launches /* host */);

@@ -28,6 +28,14 @@ SIGNATURES = {
     "qn_gram_ex": (_int, [_vp, _int, _i64, _int, _i64, _vp, _vp, _vp]),
     "qn_apply_ex": (_int, [_vp, _vp, _int, _i64, _int, _i64, _vp, _f32, _vp,
                            _vp]),
+    "qn_hinv": (_int, [_vp, _vp, _vp, _i64, _int, _f32, _vp, _vp, _vp]),
+    "qn_hinv_bf16": (_int, [_vp, _vp, _vp, _i64, _int, _f32, _vp, _vp, _vp]),
+    "qn_hinv_ex": (_int, [_vp, _vp, _int, _vp, _i64, _int, _i64, _f32, _vp, _vp,
+                          _vp]),
+    "qn_gemv_t_ex": (_int, [_vp, _int, _vp, _i64, _int, _i64, _vp, _vp]),
+    "qn_coef": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _vp]),
+    "qn_hinv_apply_ex": (_int, [_vp, _vp, _int, _vp, _i64, _int, _i64, _vp, _vp,
+                                _vp]),
     "qn_probe_copy": (_int, [_vp, _vp, _i64, _vp]),
     "qn_probe_read": (_int, [_vp, _i64, _vp, _vp]),
     "qn_probe_sink_floats": (_int, []),

@@ -37,7 +37,8 @@ int get_workspace(Workspace **out)
         const size_t b_C = align_up(sizeof(double) * QN_MAX_M * QN_MAX_M, 256);
         const size_t b_w = align_up(sizeof(double) * QN_MAX_M, 256);
         const size_t b_c = align_up(sizeof(float) * QN_MAX_M, 256);
-        ws.bytes = b_part + b_mraw + b_C + b_w + b_c;
+        const size_t b_gp = align_up(sizeof(double) * kGemvMaxBlocks * QN_MAX_M, 256);
+        ws.bytes = b_part + b_mraw + 2 * b_C + 3 * b_w + 2 * b_c + b_gp;
         if (hipMalloc(&ws.base, ws.bytes) != hipSuccess) {
             (void)hipGetLastError();
             return QN_ENOMEM;
@@ -47,7 +48,12 @@ int get_workspace(Workspace **out)
         ws.mraw = reinterpret_cast<double *>(p); p += b_mraw;
         ws.C = reinterpret_cast<double *>(p); p += b_C;
         ws.w = reinterpret_cast<double *>(p); p += b_w;
-        ws.c = reinterpret_cast<float *>(p);
+        ws.c = reinterpret_cast<float *>(p); p += b_c;
+        ws.V = reinterpret_cast<double *>(p); p += b_C;
+        ws.sigma = reinterpret_cast<double *>(p); p += b_w;
+        ws.wz = reinterpret_cast<double *>(p); p += b_w;
+        ws.cz = reinterpret_cast<float *>(p); p += b_c;
+        ws.gemv_partials = reinterpret_cast<double *>(p);
         g_ws[dev] = ws;
         g_ws_ready[dev] = true;
     }
@@ -112,6 +118,8 @@ const char *qn_kernel_name(int kernel_id)
     case QN_K_PROJECT: return "gram_project";
     case QN_K_EIG: return "eig_select";
     case QN_K_APPLY: return "apply_kernel";
+    case QN_K_GEMV: return "gemv_t";
+    case QN_K_COEF: return "coef";
     default: return "unknown";
     }
 }
@@ -175,7 +183,7 @@ int qn_apply_ex(const void *thetas, const void *grads, int dtype, int64_t n,
     const int rc = get_workspace(&ws);
     if (rc != QN_OK)
         return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, c, tau, theta_new,
+    return launch_apply(thetas, grads, dtype, n, m, ld, c, nullptr, tau, theta_new,
                         ws->cu_count, static_cast<hipStream_t>(stream));
 }
 
@@ -197,7 +205,7 @@ int qn_update_ex(const void *thetas, const void *grads, int dtype, int64_t n,
     rc = launch_eig(ws->C, ws->w, m, lambda, nullptr, nullptr, ws->c, j_out, s);
     if (rc != QN_OK)
         return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, tau, theta_new,
+    return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, nullptr, tau, theta_new,
                         ws->cu_count, s);
 }
 

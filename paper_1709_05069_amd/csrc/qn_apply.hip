@@ -17,6 +17,10 @@
 //     (Theta - G) c = sum_k c_k (t_k - h_k) - (St - Sh)/m * sum_k c_k
 // which equals the centred definition for any c (the last term vanishes when
 // the entries of c sum to zero, as they do when c comes from the eigen step).
+//
+// Operator mode (z != nullptr): the same sweep evaluates eq. (4) for an
+// arbitrary vector z, out = z + (Theta - G) c_z with c_z built from G^T z, and
+// tau, theta_bar and g_bar play no part.
 #include "qn_internal.h"
 
 namespace qn {
@@ -71,6 +75,7 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
                                              const void *__restrict__ grads,
                                              int64_t row, int m_rt, int64_t ld,
                                              const float *__restrict__ c,
+                                             const float *__restrict__ z,
                                              float csum, float tau, float inv_m,
                                              float (&res)[R])
 {
@@ -127,11 +132,23 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
                 gr[u][e] = grn[u][e];
             }
     }
+    float zz[R];
+    if (z != nullptr) {   // uniform
+        if constexpr (R == 1) {
+            zz[0] = z[row];
+        } else {
+#pragma unroll
+            for (int e = 0; e < R; e += 4) {
+                const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(z + row + e));
+                zz[e] = v.x; zz[e + 1] = v.y; zz[e + 2] = v.z; zz[e + 3] = v.w;
+            }
+        }
+    }
 #pragma unroll
     for (int e = 0; e < R; ++e) {
         const float mt = st[e] * inv_m, mh = sh[e] * inv_m;
         const float corr = acc[e] - csum * (mt - mh);
-        res[e] = (p[e] + mt) - tau * ((r[e] + mh) + corr);
+        res[e] = z != nullptr ? zz[e] + corr : (p[e] + mt) - tau * ((r[e] + mh) + corr);
     }
 }
 
@@ -141,11 +158,12 @@ __device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
                                            const void *__restrict__ grads,
                                            int64_t row, int m_rt, int64_t ld,
                                            const float *__restrict__ c,
+                                           const float *__restrict__ z,
                                            float csum, float tau, float inv_m,
                                            float *__restrict__ out)
 {
     float res[R];
-    compute_rows<DT, MC, R>(thetas, grads, row, m_rt, ld, c, csum, tau, inv_m, res);
+    compute_rows<DT, MC, R>(thetas, grads, row, m_rt, ld, c, z, csum, tau, inv_m, res);
     if constexpr (R == 1) {
         out[row] = res[0];
     } else {
@@ -160,8 +178,8 @@ __device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
 template <int DT, int MC, bool VEC>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
     const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
-    int m_rt, int64_t ld, const float *__restrict__ c, float tau,
-    float *__restrict__ out)
+    int m_rt, int64_t ld, const float *__restrict__ c,
+    const float *__restrict__ z, float tau, float *__restrict__ out)
 {
     constexpr int R = VEC ? (DT == QN_F32 ? 4 : 8) : 1;
     const int m = MC ? MC : m_rt;
@@ -174,12 +192,12 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kApplyThreads;
     for (int64_t v = static_cast<int64_t>(blockIdx.x) * kApplyThreads + threadIdx.x;
          v < nvec; v += stride)
-        apply_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, csum, tau, inv_m, out);
+        apply_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, z, csum, tau, inv_m, out);
 
     if constexpr (R > 1) {   // rows past the last full vector
         const int64_t tail0 = nvec * R;
         if (blockIdx.x == 0 && tail0 + threadIdx.x < n)
-            apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c,
+            apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c, z,
                                   csum, tau, inv_m, out);
     }
 }
@@ -214,8 +232,8 @@ template <int DT> constexpr int staged_max_steps()
 template <int DT, int MC>
 __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
     const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
-    int m_rt, int64_t ld, const float *__restrict__ c, float tau,
-    float *__restrict__ out, int steps)
+    int m_rt, int64_t ld, const float *__restrict__ c,
+    const float *__restrict__ z, float tau, float *__restrict__ out, int steps)
 {
     constexpr int kStagedThreads = StagedThreads<DT>::value;
     constexpr int R = DT == QN_F32 ? 4 : 8;        // rows per lane per step
@@ -238,7 +256,7 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
             const int64_t v = base + static_cast<int64_t>(it) * kStagedThreads + threadIdx.x;
             if (v < nvec) {
                 float res[R];
-                compute_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, csum, tau, inv_m, res);
+                compute_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, z, csum, tau, inv_m, res);
 #pragma unroll
                 for (int h = 0; h < Q; ++h)
                     stage[(it * kStagedThreads + threadIdx.x) * Q + h] =
@@ -258,13 +276,13 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
 
     const int64_t tail0 = nvec * R;                // rows past the last full vector
     if (blockIdx.x == 0 && tail0 + threadIdx.x < n)
-        apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c, csum,
+        apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c, z, csum,
                               tau, inv_m, out);
 }
 
 template <int DT, int MC>
 static void launch_mc(bool vec, int grid, const void *thetas, const void *grads,
-                      int64_t n, int m, int64_t ld, const float *c, float tau,
+                      int64_t n, int m, int64_t ld, const float *c, const float *z, float tau,
                       float *out, hipStream_t stream)
 {
     if (grid < 0) {   // staged variant, -grid blocks
@@ -283,39 +301,40 @@ static void launch_mc(bool vec, int grid, const void *thetas, const void *grads,
             attr_set = true;
         }
         hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(-grid), dim3(StagedThreads<DT>::value),
-                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, tau, out, steps);
+                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, z, tau, out, steps);
         return;
     }
     if (vec)
         hipLaunchKernelGGL((apply_kernel<DT, MC, true>), dim3(grid), dim3(kApplyThreads),
-                           0, stream, thetas, grads, n, m, ld, c, tau, out);
+                           0, stream, thetas, grads, n, m, ld, c, z, tau, out);
     else
         hipLaunchKernelGGL((apply_kernel<DT, MC, false>), dim3(grid), dim3(kApplyThreads),
-                           0, stream, thetas, grads, n, m, ld, c, tau, out);
+                           0, stream, thetas, grads, n, m, ld, c, z, tau, out);
 }
 
 template <int DT>
 static void launch_dt(bool vec, int grid, const void *thetas, const void *grads,
-                      int64_t n, int m, int64_t ld, const float *c, float tau,
+                      int64_t n, int m, int64_t ld, const float *c, const float *z, float tau,
                       float *out, hipStream_t stream)
 {
     switch (m) {
-    case 4: launch_mc<DT, 4>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
-    case 8: launch_mc<DT, 8>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
-    case 16: launch_mc<DT, 16>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
-    case 32: launch_mc<DT, 32>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
-    default: launch_mc<DT, 0>(vec, grid, thetas, grads, n, m, ld, c, tau, out, stream); break;
+    case 4: launch_mc<DT, 4>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 8: launch_mc<DT, 8>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 16: launch_mc<DT, 16>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 32: launch_mc<DT, 32>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    default: launch_mc<DT, 0>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
     }
 }
 
 int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
-                 int m, int64_t ld, const float *c, float tau, float *theta_new,
-                 int cu_count, hipStream_t stream)
+                 int m, int64_t ld, const float *c, const float *z, float tau,
+                 float *theta_new, int cu_count, hipStream_t stream)
 {
     const size_t esz = dtype == QN_F32 ? 4 : 2;
     const bool vec = (reinterpret_cast<uintptr_t>(thetas) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
                      (reinterpret_cast<uintptr_t>(theta_new) % 16 == 0) &&
+                     (reinterpret_cast<uintptr_t>(z) % 16 == 0) &&
                      ((static_cast<uint64_t>(ld) * esz) % 16 == 0);
     const int rows_per_thread = vec ? (dtype == QN_F32 ? 4 : 8) : 1;
     const int64_t per_block = static_cast<int64_t>(kApplyThreads) * rows_per_thread;
@@ -330,9 +349,9 @@ int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
 
     TraceScope ts(QN_K_APPLY, stream);
     if (dtype == QN_F32)
-        launch_dt<QN_F32>(vec, grid, thetas, grads, n, m, ld, c, tau, theta_new, stream);
+        launch_dt<QN_F32>(vec, grid, thetas, grads, n, m, ld, c, z, tau, theta_new, stream);
     else
-        launch_dt<QN_BF16>(vec, grid, thetas, grads, n, m, ld, c, tau, theta_new, stream);
+        launch_dt<QN_BF16>(vec, grid, thetas, grads, n, m, ld, c, z, tau, theta_new, stream);
     return check_launch();
 }
 

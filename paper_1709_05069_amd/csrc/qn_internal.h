@@ -23,6 +23,7 @@ constexpr int kGramMaxBlocks = 2048;
 constexpr int kTileEntries = 256;               // 16 x 16
 constexpr int kMaxTiles = 3;
 constexpr int kMaxEntries = kTileEntries * kMaxTiles;
+constexpr int kGemvMaxBlocks = 2048;
 
 // ---- per-device workspace ---------------------------------------------------
 struct Workspace {
@@ -31,6 +32,11 @@ struct Workspace {
     double *C;          // QN_MAX_M * QN_MAX_M
     double *w;          // QN_MAX_M
     float *c;           // QN_MAX_M
+    double *sigma;      // QN_MAX_M
+    double *V;          // QN_MAX_M * QN_MAX_M
+    double *wz;         // QN_MAX_M
+    float *cz;          // QN_MAX_M
+    double *gemv_partials;   // kGemvMaxBlocks * QN_MAX_M
     void *base;
     size_t bytes;
     int cu_count;
@@ -45,9 +51,17 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
 int launch_eig(const double *C, const double *w, int m, float lambda,
                double *sigma, double *V, float *c, int *j_out,
                hipStream_t stream);
+// z == nullptr: theta_new = theta_bar - tau (g_bar + (Theta - G) c);
+// z != nullptr: theta_new = z + (Theta - G) c  (tau unused)
 int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
-                 int m, int64_t ld, const float *c, float tau, float *theta_new,
-                 int cu_count, hipStream_t stream);
+                 int m, int64_t ld, const float *c, const float *z, float tau,
+                 float *theta_new, int cu_count, hipStream_t stream);
+// w = G^T z (m doubles) for the centred gradient matrix G
+int launch_gemv_t(const void *grads, int dtype, const float *z, int64_t n, int m,
+                  int64_t ld, Workspace *ws, double *w, hipStream_t stream);
+// c = sum_{k < j} v_k (v_k^T w) / sigma_k^2, j read from device memory
+int launch_coef(const double *sigma, const double *V, const int *j, const double *w,
+                int m, float *c, hipStream_t stream);
 
 // ---- tracing ------------------------------------------------------------------
 // RAII bracket: records a start/stop event pair around one kernel launch when

@@ -13,7 +13,7 @@ from . import _lib
 
 QN_F32, QN_BF16 = 0, 1
 KERNEL_NAMES = ("gram_stage1", "gram_reduce", "gram_project", "eig_select",
-                "apply_kernel")
+                "apply_kernel", "gemv_t", "coef")
 
 
 class QnError(RuntimeError):
@@ -119,6 +119,71 @@ def qn_apply(thetas, grads, c, tau, theta_new=None, stream=None):
                          c.data_ptr(), float(tau), theta_new.data_ptr(),
                          _stream(stream)), "qn_apply")
     return theta_new
+
+
+def _vector(z, n, device, name):
+    if not (z.is_cuda and z.dtype == torch.float32 and z.is_contiguous()
+            and tuple(z.shape) == (n,) and z.device == device):
+        raise QnError(f"{name} must be a contiguous float32 tensor of shape ({n},) on device")
+
+
+def qn_hinv(thetas, grads, z, lam, out=None, j_out=None, stream=None):
+    """Eq. (3)/(4) applied to an arbitrary vector z.  Returns (out, j_out)."""
+    L = _lib.load()
+    dt, m, n, ld = _worker(thetas, "thetas")
+    if (dt, m, n, ld) != _worker(grads, "grads"):
+        raise QnError("thetas and grads must agree in dtype, shape and stride")
+    _vector(z, n, thetas.device, "z")
+    out = _dev_out(out, (n,), torch.float32, thetas.device, "out")
+    j_out = _dev_out(j_out, (1,), torch.int32, thetas.device, "j_out")
+    _check(L.qn_hinv_ex(thetas.data_ptr(), grads.data_ptr(), dt, z.data_ptr(), n, m,
+                        ld, float(lam), out.data_ptr(), j_out.data_ptr(),
+                        _stream(stream)), "qn_hinv")
+    return out, j_out
+
+
+def qn_gemv_t(grads, z, stream=None):
+    """w = G^T z (m,) float64 for the centred gradient matrix."""
+    L = _lib.load()
+    dt, m, n, ld = _worker(grads, "grads")
+    _vector(z, n, grads.device, "z")
+    w = torch.empty(m, dtype=torch.float64, device=grads.device)
+    _check(L.qn_gemv_t_ex(grads.data_ptr(), dt, z.data_ptr(), n, m, ld, w.data_ptr(),
+                          _stream(stream)), "qn_gemv_t")
+    return w
+
+
+def qn_coef(sigma, V, j, w, stream=None):
+    """c (m,) fp32 from qn_eig's sigma, V, the device int j and w."""
+    L = _lib.load()
+    m = sigma.shape[0]
+    ok = (sigma.dtype == torch.float64 and V.dtype == torch.float64 and
+          w.dtype == torch.float64 and j.dtype == torch.int32 and
+          tuple(V.shape) == (m, m) and tuple(w.shape) == (m,) and j.numel() == 1 and
+          all(t.is_cuda and t.is_contiguous() for t in (sigma, V, j, w)))
+    if not ok:
+        raise QnError("qn_coef: sigma (m,), V (m, m), w (m,) float64 and j (1,) int32 on device")
+    c = torch.empty(m, dtype=torch.float32, device=sigma.device)
+    _check(L.qn_coef(sigma.data_ptr(), V.data_ptr(), j.data_ptr(), w.data_ptr(), m,
+                     c.data_ptr(), _stream(stream)), "qn_coef")
+    return c
+
+
+def qn_hinv_apply(thetas, grads, z, c, out=None, stream=None):
+    """out = z + (Theta - G) c."""
+    L = _lib.load()
+    dt, m, n, ld = _worker(thetas, "thetas")
+    if (dt, m, n, ld) != _worker(grads, "grads"):
+        raise QnError("thetas and grads must agree in dtype, shape and stride")
+    _vector(z, n, thetas.device, "z")
+    if not (c.is_cuda and c.dtype == torch.float32 and c.is_contiguous()
+            and tuple(c.shape) == (m,)):
+        raise QnError("c must be a contiguous float32 tensor of shape (m,) on device")
+    out = _dev_out(out, (n,), torch.float32, thetas.device, "out")
+    _check(L.qn_hinv_apply_ex(thetas.data_ptr(), grads.data_ptr(), dt, z.data_ptr(), n,
+                              m, ld, c.data_ptr(), out.data_ptr(), _stream(stream)),
+           "qn_hinv_apply")
+    return out
 
 
 def probe_copy(src, dst, stream=None):
