@@ -28,8 +28,12 @@
 //     wavefronts then read their operands from LDS in the lane = column layout.
 //     Measured on MI355X this load pattern sustains about 7.0 TB/s, against
 //     6.4 TB/s when each lane fetches its own column straight from HBM.
+//     For bf16 storage the fp32 matrix cores would be the bottleneck (twice the
+//     elements per byte), so that path runs on v_mfma_f32_16x16x32_bf16: the
+//     shifted fp32 value is split into two bf16 terms and the four cross
+//     products are accumulated (exact for all but widely different magnitudes).
 //   gram_stage1_elem (any alignment): each lane fetches 32 rows of its column
-//     with element loads; same arithmetic, slower.
+//     with element loads; fp32 matrix cores for both storage types; slower.
 // Stage 2 (gram_reduce): fixed-order fp64 sum of the block partials.
 // Stage 3 (gram_project): the m x m algebra above.
 #include "qn_internal.h"
@@ -106,6 +110,57 @@ __device__ __forceinline__ void lds_rows(const char *p, float (&x)[DT == QN_F32 
             x[2 * h + 1] = __uint_as_float(u[h] & 0xffff0000u);
         }
     }
+}
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+
+// d = present ? (keep_raw ? x : x - s) : 0, split into bf16 hi + lo (see the caller).
+template <int N>
+__device__ __forceinline__ void split_bf16(const float (&x)[N], const float (&s)[N],
+                                           bool present, bool keep_raw, v8bf &hi,
+                                           v8bf &lo)
+{
+    static_assert(N == 8, "one K-slice is 8 rows");
+    uint32_t hw[4], lw[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        const float d0 = present ? (keep_raw ? x[2 * h] : x[2 * h] - s[2 * h]) : 0.0f;
+        const float d1 = present ? (keep_raw ? x[2 * h + 1] : x[2 * h + 1] - s[2 * h + 1]) : 0.0f;
+        const uint32_t u0 = __float_as_uint(d0), u1 = __float_as_uint(d1);
+        hw[h] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);      // upper halves of d0, d1
+        const float l0 = d0 - __uint_as_float(u0 & 0xffff0000u);
+        const float l1 = d1 - __uint_as_float(u1 & 0xffff0000u);
+        const v2bf lp = {static_cast<__bf16>(l0), static_cast<__bf16>(l1)};
+        lw[h] = __builtin_bit_cast(uint32_t, lp);
+    }
+    const v4u hv = {hw[0], hw[1], hw[2], hw[3]}, lv = {lw[0], lw[1], lw[2], lw[3]};
+    hi = __builtin_bit_cast(v8bf, hv);
+    lo = __builtin_bit_cast(v8bf, lv);
+}
+
+// One K = 32 step of the lower-triangle tiles on the bf16 matrix cores:
+// (hi + lo)(hi + lo)^T expanded into its four products.
+template <int NT>
+__device__ __forceinline__ void gram_step_bf16(v8bf ahi, v8bf alo, v8bf bhi, v8bf blo,
+                                               v4f (&acc)[GramTiles<NT>::value])
+{
+#define QN_MFMA_BF16(A, B, C) C = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
+    QN_MFMA_BF16(ahi, ahi, acc[0]);
+    QN_MFMA_BF16(ahi, alo, acc[0]);
+    QN_MFMA_BF16(alo, ahi, acc[0]);
+    QN_MFMA_BF16(alo, alo, acc[0]);
+    if constexpr (NT == 2) {
+        QN_MFMA_BF16(bhi, ahi, acc[1]);
+        QN_MFMA_BF16(bhi, alo, acc[1]);
+        QN_MFMA_BF16(blo, ahi, acc[1]);
+        QN_MFMA_BF16(blo, alo, acc[1]);
+        QN_MFMA_BF16(bhi, bhi, acc[2]);
+        QN_MFMA_BF16(bhi, blo, acc[2]);
+        QN_MFMA_BF16(blo, bhi, acc[2]);
+        QN_MFMA_BF16(blo, blo, acc[2]);
+    }
+#undef QN_MFMA_BF16
 }
 
 template <int DT, int NT>
@@ -202,13 +257,27 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
             lds_rows<DT>(stage + byte0 + 16 * i, s);             // column 0: the pivot
             if constexpr (NT == 2)
                 lds_rows<DT>(stage + (col + 16) * kColPitch + byte0 + 16 * i, b);
+            if constexpr (DT == QN_F32) {
 #pragma unroll
-            for (int e = 0; e < RPV; ++e) {
-                const float da = has_a ? (is_pivot ? a[e] : a[e] - s[e]) : 0.0f;
-                float db = 0.0f;
+                for (int e = 0; e < RPV; ++e) {
+                    const float da = has_a ? (is_pivot ? a[e] : a[e] - s[e]) : 0.0f;
+                    float db = 0.0f;
+                    if constexpr (NT == 2)
+                        db = has_b ? b[e] - s[e] : 0.0f;
+                    gram_step<NT>(da, db, acc);
+                }
+            } else {
+                // bf16 storage: the 8 rows a lane just read are one K-slice of
+                // v_mfma_f32_16x16x32_bf16.  The shifted value d = x - s (exact in
+                // fp32) is split as hi + lo, hi = its upper 16 bits (a bf16), lo =
+                // bf16(d - hi): exact whenever d has at most 16 significant bits
+                // (always, unless x and s differ by more than 2^8 in magnitude),
+                // else good to 2^-16.  All four hi/lo products are accumulated.
+                v8bf ahi, alo, bhi = {}, blo = {};
+                split_bf16<RPV>(a, s, has_a, is_pivot, ahi, alo);
                 if constexpr (NT == 2)
-                    db = has_b ? b[e] - s[e] : 0.0f;
-                gram_step<NT>(da, db, acc);
+                    split_bf16<RPV>(b, s, has_b, false, bhi, blo);
+                gram_step_bf16<NT>(ahi, alo, bhi, blo, acc);
             }
         }
 #pragma unroll
