@@ -280,31 +280,25 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
                               tau, inv_m, out);
 }
 
+enum class ApplyShape { kElementwise, kDirect, kStaged };
+
 template <int DT, int MC>
-static void launch_mc(bool vec, int grid, const void *thetas, const void *grads,
+static void launch_mc(ApplyShape shape, int grid, const void *thetas, const void *grads,
                       int64_t n, int m, int64_t ld, const float *c, const float *z, float tau,
                       float *out, hipStream_t stream)
 {
-    if (grid < 0) {   // staged variant, -grid blocks
+    if (shape == ApplyShape::kStaged) {
         // slab length: every block gets the same number of (nearly) full slabs
         constexpr int R = DT == QN_F32 ? 4 : 8;
-        const int64_t per_block =
-            (n / R + static_cast<int64_t>(-grid) * StagedThreads<DT>::value - 1) /
-            (static_cast<int64_t>(-grid) * StagedThreads<DT>::value);       // lane-steps per thread
-        const int64_t rounds = (per_block + staged_max_steps<DT>() - 1) / staged_max_steps<DT>();
-        const int steps = static_cast<int>((per_block + rounds - 1) / rounds);
-        static bool attr_set = false;   // per instantiation
-        if (!attr_set) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(apply_staged<DT, MC>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      kStagedLdsBytes);
-            attr_set = true;
-        }
-        hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(-grid), dim3(StagedThreads<DT>::value),
+        const int64_t lanes = static_cast<int64_t>(grid) * StagedThreads<DT>::value;
+        const int64_t per_thread = (n / R + lanes - 1) / lanes;            // lane-steps
+        const int64_t rounds = (per_thread + staged_max_steps<DT>() - 1) / staged_max_steps<DT>();
+        const int steps = static_cast<int>((per_thread + rounds - 1) / rounds);
+        hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(grid), dim3(StagedThreads<DT>::value),
                            kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, z, tau, out, steps);
         return;
     }
-    if (vec)
+    if (shape == ApplyShape::kDirect)
         hipLaunchKernelGGL((apply_kernel<DT, MC, true>), dim3(grid), dim3(kApplyThreads),
                            0, stream, thetas, grads, n, m, ld, c, z, tau, out);
     else
@@ -313,17 +307,33 @@ static void launch_mc(bool vec, int grid, const void *thetas, const void *grads,
 }
 
 template <int DT>
-static void launch_dt(bool vec, int grid, const void *thetas, const void *grads,
+static void launch_dt(ApplyShape shape, int grid, const void *thetas, const void *grads,
                       int64_t n, int m, int64_t ld, const float *c, const float *z, float tau,
                       float *out, hipStream_t stream)
 {
     switch (m) {
-    case 4: launch_mc<DT, 4>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    case 8: launch_mc<DT, 8>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    case 16: launch_mc<DT, 16>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    case 32: launch_mc<DT, 32>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    default: launch_mc<DT, 0>(vec, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 4: launch_mc<DT, 4>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 8: launch_mc<DT, 8>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 16: launch_mc<DT, 16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 32: launch_mc<DT, 32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    default: launch_mc<DT, 0>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
     }
+}
+
+// Per-device opt-in to 128 KiB of dynamic LDS for the staged kernels.
+int setup_apply_kernels()
+{
+    bool ok = true;
+#define QN_OPT_IN(DTV, MCV)                                                            \
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(apply_staged<DTV, MCV>), \
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,        \
+                                   kStagedLdsBytes) == hipSuccess
+    QN_OPT_IN(QN_F32, 0); QN_OPT_IN(QN_F32, 4); QN_OPT_IN(QN_F32, 8);
+    QN_OPT_IN(QN_F32, 16); QN_OPT_IN(QN_F32, 32);
+    QN_OPT_IN(QN_BF16, 0); QN_OPT_IN(QN_BF16, 4); QN_OPT_IN(QN_BF16, 8);
+    QN_OPT_IN(QN_BF16, 16); QN_OPT_IN(QN_BF16, 32);
+#undef QN_OPT_IN
+    return ok ? QN_OK : QN_ELAUNCH;
 }
 
 int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
@@ -341,17 +351,20 @@ int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
     int64_t want = (n + per_block - 1) / per_block;
     const int64_t cap = static_cast<int64_t>(cu_count) * 8;
     int grid = static_cast<int>(want < cap ? want : cap);
+    ApplyShape shape = vec ? ApplyShape::kDirect : ApplyShape::kElementwise;
     // large aligned problems: one block per CU with LDS-staged output bursts
     // (a full slab covers 32768 rows; worth it once every CU gets at least one)
     const int64_t slab_rows = kStagedLdsBytes / 4;
-    if (vec && n >= slab_rows * cu_count)
-        grid = -cu_count;
+    if (vec && n >= slab_rows * cu_count) {
+        shape = ApplyShape::kStaged;
+        grid = cu_count;
+    }
 
     TraceScope ts(QN_K_APPLY, stream);
     if (dtype == QN_F32)
-        launch_dt<QN_F32>(vec, grid, thetas, grads, n, m, ld, c, z, tau, theta_new, stream);
+        launch_dt<QN_F32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, theta_new, stream);
     else
-        launch_dt<QN_BF16>(vec, grid, thetas, grads, n, m, ld, c, z, tau, theta_new, stream);
+        launch_dt<QN_BF16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, theta_new, stream);
     return check_launch();
 }
 

@@ -462,14 +462,6 @@ static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t 
         const int64_t num_tiles = (n + StreamRows<DT>::value - 1) / StreamRows<DT>::value;
         const int64_t cap = static_cast<int64_t>(cu_count) * 2;   // two 65 KB blocks per CU
         grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
-        static bool attr_set = false;   // per instantiation
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(gram_stage1_stream<DT, NT>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    kStreamLdsBytes) != hipSuccess)
-                return -1;
-            attr_set = true;
-        }
         hipLaunchKernelGGL((gram_stage1_stream<DT, NT>), dim3(grid), dim3(kGramThreads),
                            kStreamLdsBytes, stream, grads, n, m, ld, partials);
     } else {
@@ -481,6 +473,23 @@ static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t 
                            stream, grads, n, m, ld, partials);
     }
     return grid;
+}
+
+// The streaming kernels use more than the default 64 KiB of dynamic LDS; the
+// opt-in is per device and is made once when the device's workspace is set up.
+int setup_gram_kernels()
+{
+    bool ok = true;
+#define QN_OPT_IN(K)                                                                   \
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(K),                  \
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,        \
+                                   kStreamLdsBytes) == hipSuccess
+    QN_OPT_IN((gram_stage1_stream<QN_F32, 1>));
+    QN_OPT_IN((gram_stage1_stream<QN_F32, 2>));
+    QN_OPT_IN((gram_stage1_stream<QN_BF16, 1>));
+    QN_OPT_IN((gram_stage1_stream<QN_BF16, 2>));
+#undef QN_OPT_IN
+    return ok ? QN_OK : QN_ELAUNCH;
 }
 
 int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,

@@ -45,6 +45,10 @@ struct Workspace {
 // Returns the current device's workspace (allocating it on first use).
 int get_workspace(Workspace **out);
 
+// ---- per-device kernel set-up (called once when a device's workspace is made) --
+int setup_gram_kernels();
+int setup_apply_kernels();
+
 // ---- kernel launchers (each enqueues on `stream`, returns a qn_status) ------
 int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
                 Workspace *ws, double *C, double *w, hipStream_t stream);
