@@ -94,3 +94,44 @@ def test_binding_rejects_bad_tensors():
     big = torch.zeros((33, 64), device=DEV)
     with pytest.raises(qn.QnError):
         qn.qn_gram(big)                                  # m > QN_MAX_M
+
+
+def test_update_can_be_captured_in_a_hip_graph_and_replayed():
+    # after qn_init the step allocates nothing and records no memset, so a
+    # caller may capture it; every replay must reproduce the eager result, also
+    # with fresh inputs copied into the captured buffers between replays
+    wl, th, gr = _inputs(200_000, "resnet50")
+    qn.qn_init()
+    out = torch.empty(wl.n, dtype=torch.float32, device=DEV)
+    j = torch.zeros(1, dtype=torch.int32, device=DEV)
+    eager, je = qn.qn_update(th, gr, wl.tau, wl.lam)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        qn.qn_update(th, gr, wl.tau, wl.lam, out, j)      # warm-up on the side stream
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        qn.qn_update(th, gr, wl.tau, wl.lam, out, j)
+    for rep in range(3):
+        out.zero_()
+        j.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager) and int(j.item()) == int(je.item())
+        # eager work of the program between replays
+        _ = qn.qn_gram(gr)
+        torch.cuda.synchronize()
+    # new inputs in the captured buffers
+    wl2 = synth.WORKLOADS["resnet50"].scaled(200_000)
+    from dataclasses import replace
+    th2, gr2 = synth.make_worker_states(replace(wl2, seed=5), DEV)
+    th.copy_(th2)
+    gr.copy_(gr2)
+    eager2, je2 = qn.qn_update(th, gr, wl.tau, wl.lam)
+    g.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, eager2) and int(j.item()) == int(je2.item())
+    assert not torch.equal(eager2, eager)
