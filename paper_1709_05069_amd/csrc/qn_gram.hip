@@ -388,8 +388,19 @@ __global__ __launch_bounds__(64 * kReduceSlices) void gram_reduce(
     __shared__ double part[kReduceSlices][64];
     const int e = blockIdx.x * 64 + (threadIdx.x & 63);
     const int slice = threadIdx.x >> 6;
+    // eight loads in flight, added in the order of p (the order fixes the bits)
     double s = 0.0;
-    for (int p = slice; p < num_partials; p += kReduceSlices)
+    int p = slice;
+    for (; p + 7 * kReduceSlices < num_partials; p += 8 * kReduceSlices) {
+        double v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            v[u] = partials[static_cast<int64_t>(p + u * kReduceSlices) * entries + e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            s += v[u];
+    }
+    for (; p < num_partials; p += kReduceSlices)
         s += partials[static_cast<int64_t>(p) * entries + e];
     part[slice][threadIdx.x & 63] = s;
     __syncthreads();
