@@ -64,6 +64,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2_small")
     ap.add_argument("--n", type=int, default=0, help="override the row count")
+    ap.add_argument("--m", type=int, default=0, help="override the worker count")
+    ap.add_argument("--no-read-probe", action="store_true",
+                    help="skip the plain read-stream probe (8 GiB) that gives "
+                         "the practical HBM read ceiling of this device")
     ap.add_argument("--cpu-sample-rows", type=int, default=40_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -86,6 +90,9 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     if args.n:
         wl = wl.scaled(args.n)
+    if args.m:
+        from dataclasses import replace
+        wl = replace(wl, m=args.m, name=f"{wl.name}@m={args.m}")
     esz = 4 if wl.storage == "f32" else 2
 
     t0 = time.perf_counter()
@@ -148,6 +155,24 @@ def main():
         "frac_of_peak": total_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
 
+    read_probe = None
+    if not args.no_read_probe:
+        # practical ceiling: the library's plain read kernel (contiguous chunk per
+        # block, non-temporal loads) over 8 GiB, best of 5: context for the
+        # fractions of the 8 TB/s peak
+        buf = torch.empty(2 << 30, dtype=torch.float32, device="cuda:0").fill_(1.0)
+        best = float("inf")
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            qn.probe_read(buf)
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        read_probe = {"bytes": buf.numel() * 4, "best_ms": best,
+                      "GBps": buf.numel() * 4 / (best * 1e-3) / 1e9}
+        del buf
+
     out = {
         "metric": METRIC, "value": 1e3 / ms_per_step, "unit": "updates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -158,6 +183,7 @@ def main():
                                f"{wl.storage} storage, lambda={wl.lam}, tau={wl.tau}",
                    "j": j},
         "roofline": roofline, "whole_update": whole, "kernels": kernels,
+        "read_probe": read_probe,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, thetas, grads, args.cpu_sample_rows)

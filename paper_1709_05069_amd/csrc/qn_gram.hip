@@ -22,18 +22,19 @@
 //   tiles).  MFMA accumulators run in fp32 over one tile and are then added to
 //   per-lane fp64 totals; waves are combined through LDS in a fixed order and
 //   each block writes one partial.  No atomics.
-//   gram_stage1_stream (aligned input): HBM -> LDS with coalesced direct-to-LDS
-//     128-bit loads carrying the non-temporal hint (every wave instruction moves
-//     1 KiB of one column), two LDS stages per block, two blocks per CU; the
-//     wavefronts then read their operands from LDS in the lane = column layout.
+//   gram_stage1_stream: HBM -> LDS with coalesced direct-to-LDS loads carrying the
+//     non-temporal hint (128-bit per lane when the columns are 16-byte aligned:
+//     every wave instruction moves 1 KiB of one column; element-sized per lane
+//     otherwise), two LDS stages per block, two blocks per CU; the wavefronts
+//     then read their operands from LDS in the lane = column layout.
 //     Measured on MI355X this load pattern sustains about 7.0 TB/s, against
 //     6.4 TB/s when each lane fetches its own column straight from HBM.
 //     For bf16 storage the fp32 matrix cores would be the bottleneck (twice the
 //     elements per byte), so that path runs on v_mfma_f32_16x16x32_bf16: the
 //     shifted fp32 value is split into two bf16 terms and the four cross
 //     products are accumulated (exact for all but widely different magnitudes).
-//   gram_stage1_elem (any alignment): each lane fetches 32 rows of its column
-//     with element loads; fp32 matrix cores for both storage types; slower.
+//     (Unaligned bf16 input stays on the fp32 matrix cores: 2-byte direct-to-LDS
+//     loads land one value per dword.)
 // Stage 2 (gram_reduce): fixed-order fp64 sum of the block partials.
 // Stage 3 (gram_project): the m x m algebra above.
 #include "qn_internal.h"
@@ -92,15 +93,25 @@ constexpr int kColPitch = 1040;                       // bytes per column slot
 constexpr int kStageBytes = QN_MAX_M * kColPitch;     // 33 280
 constexpr int kStreamLdsBytes = 2 * kStageBytes;      // two stages
 
-template <int DT> struct StreamRows { static constexpr int value = (DT == QN_F32) ? 256 : 512; };
+// Rows per tile: a column's tile is 1 KiB in LDS.  bf16 inputs that are not
+// 16-byte aligned arrive through 2-byte direct-to-LDS loads, which the hardware
+// stores zero-extended, one per dword: their LDS format is 4 bytes per row.
+template <int DT, bool ALIGNED> struct StreamRows {
+    static constexpr int value = (DT == QN_F32 || !ALIGNED) ? 256 : 512;
+};
 
-// 16 bytes of one column from LDS as fp32 row values.
-template <int DT>
-__device__ __forceinline__ void lds_rows(const char *p, float (&x)[DT == QN_F32 ? 4 : 8])
+// 16 bytes of one column from LDS as fp32 row values.  FMT 0: fp32; 1: packed
+// bf16 (8 rows); 2: bf16 zero-extended to one dword per row (4 rows).
+template <int FMT>
+__device__ __forceinline__ void lds_rows(const char *p, float (&x)[FMT == 1 ? 8 : 4])
 {
-    if constexpr (DT == QN_F32) {
+    if constexpr (FMT == 0) {
         const v4f v = *reinterpret_cast<const v4f *>(p);
         x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+    } else if constexpr (FMT == 2) {
+        const v4u v = *reinterpret_cast<const v4u *>(p);
+        x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.y << 16);
+        x[2] = __uint_as_float(v.z << 16); x[3] = __uint_as_float(v.w << 16);
     } else {
         const v4u v = *reinterpret_cast<const v4u *>(p);
         const uint32_t u[4] = {v.x, v.y, v.z, v.w};
@@ -163,15 +174,22 @@ __device__ __forceinline__ void gram_step_bf16(v8bf ahi, v8bf alo, v8bf bhi, v8b
 #undef QN_MFMA_BF16
 }
 
-template <int DT, int NT>
+// ALIGNED: every column start is 16-byte aligned, one 128-bit load per lane moves
+// a column's whole tile (1 KiB) per wave instruction.  Otherwise the same tile is
+// brought in with element-sized direct-to-LDS loads (64 consecutive rows per
+// wave instruction): still coalesced, any alignment, more instructions.
+template <int DT, int NT, bool ALIGNED>
 __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     const void *__restrict__ grads, int64_t n, int m, int64_t ld,
     double *__restrict__ partials)
 {
     constexpr int TILES = GramTiles<NT>::value;
-    constexpr int ROWS = StreamRows<DT>::value;          // rows per tile
-    constexpr int ESZ = (DT == QN_F32) ? 4 : 2;
-    constexpr int RPV = 16 / ESZ;                        // rows per 16-byte vector
+    constexpr int ROWS = StreamRows<DT, ALIGNED>::value; // rows per tile
+    constexpr int ESZ = (DT == QN_F32) ? 4 : 2;          // element size in memory
+    constexpr bool WIDE = DT == QN_BF16 && !ALIGNED;     // bf16 kept one per dword in LDS
+    constexpr int LESZ = WIDE ? 4 : ESZ;                 // element size in LDS
+    constexpr int FMT = DT == QN_F32 ? 0 : (WIDE ? 2 : 1);
+    constexpr int RPV = 16 / LESZ;                       // rows per 16-byte LDS vector
     constexpr int COLS_PER_WAVE = QN_MAX_M / kGramWaves; // columns a wave loads
     constexpr int VEC_PER_GROUP = ROWS / kGramWaves / 4 / RPV;   // 2 either way
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -198,9 +216,22 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
             for (int jc = 0; jc < COLS_PER_WAVE; ++jc) {
                 const int c = wave * COLS_PER_WAVE + jc;
                 if (c < m) {
-                    const char *g = base + (static_cast<int64_t>(c) * ld + row0) * ESZ + lane * 16;
-                    __builtin_amdgcn_global_load_lds(QN_GPTR(g), QN_LPTR(stage + c * kColPitch),
-                                                     16, 0, /*nt*/ 2);
+                    const char *g = base + (static_cast<int64_t>(c) * ld + row0) * ESZ;
+                    if constexpr (ALIGNED) {
+                        __builtin_amdgcn_global_load_lds(QN_GPTR(g + lane * 16),
+                                                         QN_LPTR(stage + c * kColPitch),
+                                                         16, 0, /*nt*/ 2);
+                    } else {
+#pragma unroll
+                        for (int part = 0; part < ROWS / 64; ++part) {
+                            const char *gp = g + (part * 64 + lane) * ESZ;
+                            char *lp = stage + c * kColPitch + part * 64 * LESZ;
+                            if constexpr (DT == QN_F32)
+                                __builtin_amdgcn_global_load_lds(QN_GPTR(gp), QN_LPTR(lp), 4, 0, 2);
+                            else
+                                __builtin_amdgcn_global_load_lds(QN_GPTR(gp), QN_LPTR(lp), 2, 0, 2);
+                        }
+                    }
                 }
             }
         } else {
@@ -211,14 +242,17 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
                     continue;
                 for (int e = 0; e < RPV; ++e) {
                     const int64_t r = row0 + lane * RPV + e;
-                    char *dst = stage + c * kColPitch + (lane * RPV + e) * ESZ;
+                    char *dst = stage + c * kColPitch + (lane * RPV + e) * LESZ;
                     if constexpr (DT == QN_F32) {
                         const float *src = reinterpret_cast<const float *>(base);
                         *reinterpret_cast<float *>(dst) = r < n ? src[c * ld + r] : 0.0f;
                     } else {
                         const uint16_t *src = reinterpret_cast<const uint16_t *>(base);
-                        *reinterpret_cast<uint16_t *>(dst) =
-                            r < n ? src[c * ld + r] : static_cast<uint16_t>(0);
+                        const uint16_t v = r < n ? src[c * ld + r] : static_cast<uint16_t>(0);
+                        if constexpr (WIDE)
+                            *reinterpret_cast<uint32_t *>(dst) = v;
+                        else
+                            *reinterpret_cast<uint16_t *>(dst) = v;
                     }
                 }
             }
@@ -245,7 +279,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
 
         const char *stage = lds + (k & 1) * kStageBytes;
         // this wave's rows: its share of the tile; this lane group's: a quarter of that
-        const int byte0 = (wave * (ROWS / kGramWaves) + group * (ROWS / kGramWaves / 4)) * ESZ;
+        const int byte0 = (wave * (ROWS / kGramWaves) + group * (ROWS / kGramWaves / 4)) * LESZ;
         v4f acc[TILES];
 #pragma unroll
         for (int t = 0; t < TILES; ++t)
@@ -253,11 +287,11 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
 #pragma unroll
         for (int i = 0; i < VEC_PER_GROUP; ++i) {
             float a[RPV], b[RPV], s[RPV];
-            lds_rows<DT>(stage + col * kColPitch + byte0 + 16 * i, a);
-            lds_rows<DT>(stage + byte0 + 16 * i, s);             // column 0: the pivot
+            lds_rows<FMT>(stage + col * kColPitch + byte0 + 16 * i, a);
+            lds_rows<FMT>(stage + byte0 + 16 * i, s);            // column 0: the pivot
             if constexpr (NT == 2)
-                lds_rows<DT>(stage + (col + 16) * kColPitch + byte0 + 16 * i, b);
-            if constexpr (DT == QN_F32) {
+                lds_rows<FMT>(stage + (col + 16) * kColPitch + byte0 + 16 * i, b);
+            if constexpr (FMT != 1) {
 #pragma unroll
                 for (int e = 0; e < RPV; ++e) {
                     const float da = has_a ? (is_pivot ? a[e] : a[e] - s[e]) : 0.0f;
@@ -288,94 +322,6 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     }
     __syncthreads();   // all reads of the stages are done: reuse them for the reduction
     write_block_partial<TILES>(tot, reinterpret_cast<double *>(lds), partials);
-}
-
-// ---------------------------------------------------------------------------
-// Fallback for inputs that are not 16-byte aligned: lane = column, 32 rows per
-// lane per tile fetched with guarded element loads.
-constexpr int kRowsPerLane = 32;                  // per column, per tile
-constexpr int kTileRows = 4 * kRowsPerLane;       // 4 row groups per wavefront
-
-template <int DT>
-__device__ __forceinline__ void load_rows_elem(const void *base, int64_t elem0,
-                                               int64_t rows_valid,
-                                               float (&x)[kRowsPerLane])
-{
-    if constexpr (DT == QN_F32) {
-        const float *p = static_cast<const float *>(base) + elem0;
-#pragma unroll
-        for (int i = 0; i < kRowsPerLane; ++i)
-            x[i] = (i < rows_valid) ? p[i] : 0.0f;
-    } else {
-        const uint16_t *p = static_cast<const uint16_t *>(base) + elem0;
-#pragma unroll
-        for (int i = 0; i < kRowsPerLane; ++i)
-            x[i] = (i < rows_valid) ? __uint_as_float(static_cast<uint32_t>(p[i]) << 16)
-                                    : 0.0f;
-    }
-}
-
-template <int DT, int NT>
-__global__ __launch_bounds__(kGramThreads) void gram_stage1_elem(
-    const void *__restrict__ grads, int64_t n, int m, int64_t ld,
-    double *__restrict__ partials)
-{
-    constexpr int TILES = GramTiles<NT>::value;
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int col = lane & 15;
-    const int group = lane >> 4;
-    const bool has_a = col < m;
-    const bool has_b = (NT == 2) && (col + 16 < m);
-
-    double tot[TILES][4];
-#pragma unroll
-    for (int t = 0; t < TILES; ++t)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            tot[t][r] = 0.0;
-
-    const int64_t num_tiles = (n + kTileRows - 1) / kTileRows;
-    const int64_t wave_stride = static_cast<int64_t>(gridDim.x) * kGramWaves;
-    for (int64_t tile = static_cast<int64_t>(blockIdx.x) * kGramWaves + wave;
-         tile < num_tiles; tile += wave_stride) {
-        const int64_t row0 = tile * kTileRows + group * kRowsPerLane;
-        float a[kRowsPerLane], b[kRowsPerLane];
-#pragma unroll
-        for (int i = 0; i < kRowsPerLane; ++i) {
-            a[i] = 0.0f;
-            b[i] = 0.0f;
-        }
-        int64_t valid = n - row0;
-        valid = valid < 0 ? 0 : (valid > kRowsPerLane ? kRowsPerLane : valid);
-        if (has_a && valid > 0)
-            load_rows_elem<DT>(grads, col * ld + row0, valid, a);
-        if (has_b && valid > 0)
-            load_rows_elem<DT>(grads, (col + 16) * ld + row0, valid, b);
-
-        // pivot shift: lane (group*16) holds column 0 of this row group
-        const int src = (lane & 48) << 2;
-        v4f acc[TILES];
-#pragma unroll
-        for (int t = 0; t < TILES; ++t)
-            acc[t] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int i = 0; i < kRowsPerLane; ++i) {
-            const float s = __int_as_float(
-                __builtin_amdgcn_ds_bpermute(src, __float_as_int(a[i])));
-            const float da = (col == 0) ? a[i] : (has_a ? a[i] - s : 0.0f);
-            const float db = has_b ? b[i] - s : 0.0f;
-            gram_step<NT>(da, db, acc);
-        }
-#pragma unroll
-        for (int t = 0; t < TILES; ++t)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                tot[t][r] += static_cast<double>(acc[t][r]);
-    }
-
-    __shared__ double red[kGramWaves * TILES * 4 * 64];
-    write_block_partial<TILES>(tot, red, partials);
 }
 
 // Fixed-order fp64 sum over the block partials.  Block b owns 64 entries; 16
@@ -468,21 +414,16 @@ template <int DT, int NT>
 static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t n,
                          int m, int64_t ld, double *partials, hipStream_t stream)
 {
-    int grid;
-    if (aligned) {
-        const int64_t num_tiles = (n + StreamRows<DT>::value - 1) / StreamRows<DT>::value;
-        const int64_t cap = static_cast<int64_t>(cu_count) * 2;   // two 65 KB blocks per CU
-        grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
-        hipLaunchKernelGGL((gram_stage1_stream<DT, NT>), dim3(grid), dim3(kGramThreads),
+    const int rows = aligned ? StreamRows<DT, true>::value : StreamRows<DT, false>::value;
+    const int64_t num_tiles = (n + rows - 1) / rows;
+    const int64_t cap = static_cast<int64_t>(cu_count) * 2;   // two 65 KB blocks per CU
+    const int grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
+    if (aligned)
+        hipLaunchKernelGGL((gram_stage1_stream<DT, NT, true>), dim3(grid), dim3(kGramThreads),
                            kStreamLdsBytes, stream, grads, n, m, ld, partials);
-    } else {
-        const int64_t num_tiles = (n + kTileRows - 1) / kTileRows;
-        const int64_t want = (num_tiles + kGramWaves - 1) / kGramWaves;
-        const int64_t cap = static_cast<int64_t>(cu_count) * 2;
-        grid = static_cast<int>(want < cap ? want : cap);
-        hipLaunchKernelGGL((gram_stage1_elem<DT, NT>), dim3(grid), dim3(kGramThreads), 0,
-                           stream, grads, n, m, ld, partials);
-    }
+    else
+        hipLaunchKernelGGL((gram_stage1_stream<DT, NT, false>), dim3(grid), dim3(kGramThreads),
+                           kStreamLdsBytes, stream, grads, n, m, ld, partials);
     return grid;
 }
 
@@ -495,10 +436,14 @@ int setup_gram_kernels()
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(K),                  \
                                    hipFuncAttributeMaxDynamicSharedMemorySize,        \
                                    kStreamLdsBytes) == hipSuccess
-    QN_OPT_IN((gram_stage1_stream<QN_F32, 1>));
-    QN_OPT_IN((gram_stage1_stream<QN_F32, 2>));
-    QN_OPT_IN((gram_stage1_stream<QN_BF16, 1>));
-    QN_OPT_IN((gram_stage1_stream<QN_BF16, 2>));
+    QN_OPT_IN((gram_stage1_stream<QN_F32, 1, true>));
+    QN_OPT_IN((gram_stage1_stream<QN_F32, 2, true>));
+    QN_OPT_IN((gram_stage1_stream<QN_BF16, 1, true>));
+    QN_OPT_IN((gram_stage1_stream<QN_BF16, 2, true>));
+    QN_OPT_IN((gram_stage1_stream<QN_F32, 1, false>));
+    QN_OPT_IN((gram_stage1_stream<QN_F32, 2, false>));
+    QN_OPT_IN((gram_stage1_stream<QN_BF16, 1, false>));
+    QN_OPT_IN((gram_stage1_stream<QN_BF16, 2, false>));
 #undef QN_OPT_IN
     return ok ? QN_OK : QN_ELAUNCH;
 }
