@@ -25,10 +25,11 @@
  *   is fp32, or bfloat16 for the *_bf16 entry points (accumulation is fp32 /
  *   fp64 either way, theta_new is always fp32).  Small matrices are stored
  *   the same way: V[k*m + r] is component r of v_k.
- * Alignment: any element-aligned pointer and any n work.  The 128-bit load
- *   path is taken when the base pointers are 16-byte aligned and ld*sizeof(elem)
- *   is a multiple of 16; otherwise a slower element-wise path computes the same
- *   result.
+ * Alignment: any element-aligned pointer and any n work.  Fastest when the
+ *   base pointers are 16-byte aligned and ld*sizeof(elem) is a multiple of 16
+ *   (true whenever n is a multiple of 4, or 8 for bfloat16, and ld = n);
+ *   otherwise the Gram pass fetches element-wise and 128-bit accesses straddle
+ *   cache lines: the same result, about 15 % slower at the 124M x 32 size.
  * Aliasing: theta_new must not overlap an input.
  * Streams: all work is enqueued on `stream` (a hipStream_t passed as void*;
  *   NULL is the default stream) and the call returns without synchronising.

@@ -27,6 +27,11 @@ namespace qn {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+// 128-bit global accesses at element alignment: gfx950 under HSA runs with
+// unaligned global access enabled, so one dwordx4 instruction serves any
+// element-aligned address (columns of a matrix whose n is not a multiple of 4).
+typedef v4f v4f_elem __attribute__((aligned(4)));
+typedef v4u v4u_elem __attribute__((aligned(2)));
 
 constexpr int kApplyThreads = 256;
 // worker columns whose loads are issued together (two such chunks are in flight)
@@ -46,7 +51,7 @@ __device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (
     if constexpr (DT == QN_F32) {
         const float *p = static_cast<const float *>(base) + elem;
         if constexpr (R == 4) {
-            const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+            const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f_elem *>(p));
             x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
         } else {
             static_assert(R == 1, "fp32 rows per lane");
@@ -55,7 +60,7 @@ __device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (
     } else {
         const uint16_t *p = static_cast<const uint16_t *>(base) + elem;
         if constexpr (R == 8) {
-            const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
+            const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u_elem *>(p));
             const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
@@ -139,7 +144,7 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
         } else {
 #pragma unroll
             for (int e = 0; e < R; e += 4) {
-                const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(z + row + e));
+                const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f_elem *>(z + row + e));
                 zz[e] = v.x; zz[e + 1] = v.y; zz[e + 2] = v.z; zz[e + 3] = v.w;
             }
         }
@@ -170,7 +175,7 @@ __device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
 #pragma unroll
         for (int e = 0; e < R; e += 4) {
             v4f v = {res[e], res[e + 1], res[e + 2], res[e + 3]};
-            __builtin_nontemporal_store(v, reinterpret_cast<v4f *>(out + row + e));
+            __builtin_nontemporal_store(v, reinterpret_cast<v4f_elem *>(out + row + e));
         }
     }
 }
@@ -265,7 +270,7 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
         }
         __syncthreads();
         // the slab's results are contiguous in memory: rows [base*R, (base+slab)*R)
-        v4f *dst = reinterpret_cast<v4f *>(out) + base * Q;
+        v4f_elem *dst = reinterpret_cast<v4f_elem *>(out) + base * Q;
         const int64_t left = (nvec - base) * Q;
         const int count = static_cast<int>(left < slab * Q ? left : slab * Q);
 #pragma unroll 1
@@ -340,12 +345,10 @@ int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
                  int m, int64_t ld, const float *c, const float *z, float tau,
                  float *theta_new, int cu_count, hipStream_t stream)
 {
-    const size_t esz = dtype == QN_F32 ? 4 : 2;
-    const bool vec = (reinterpret_cast<uintptr_t>(thetas) % 16 == 0) &&
-                     (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
-                     (reinterpret_cast<uintptr_t>(theta_new) % 16 == 0) &&
-                     (reinterpret_cast<uintptr_t>(z) % 16 == 0) &&
-                     ((static_cast<uint64_t>(ld) * esz) % 16 == 0);
+    // 128-bit accesses work at element alignment (see v4f_elem), so the wide path
+    // serves every input; the element-wise kernel remains as the shape for
+    // problems smaller than one vector per lane
+    const bool vec = n >= (dtype == QN_F32 ? 4 : 8);
     const int rows_per_thread = vec ? (dtype == QN_F32 ? 4 : 8) : 1;
     const int64_t per_block = static_cast<int64_t>(kApplyThreads) * rows_per_thread;
     int64_t want = (n + per_block - 1) / per_block;

@@ -12,6 +12,10 @@ namespace qn {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+// 128-bit global loads at element alignment (unaligned global access is enabled
+// on gfx950 under HSA), so the wide path serves any element-aligned input
+typedef v4f v4f_elem __attribute__((aligned(4)));
+typedef v4u v4u_elem __attribute__((aligned(2)));
 
 constexpr int kGemvThreads = 256;
 
@@ -21,7 +25,7 @@ __device__ __forceinline__ void gemv_load(const void *base, int64_t elem, float 
     if constexpr (DT == QN_F32) {
         const float *p = static_cast<const float *>(base) + elem;
         if constexpr (R == 4) {
-            const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+            const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f_elem *>(p));
             x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
         } else {
             x[0] = *p;
@@ -29,7 +33,7 @@ __device__ __forceinline__ void gemv_load(const void *base, int64_t elem, float 
     } else {
         const uint16_t *p = static_cast<const uint16_t *>(base) + elem;
         if constexpr (R == 8) {
-            const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(p));
+            const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u_elem *>(p));
             const uint32_t u[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
@@ -56,7 +60,7 @@ __device__ __forceinline__ void gemv_rows(const void *__restrict__ grads,
     } else {
 #pragma unroll
         for (int e = 0; e < R; e += 4) {
-            const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(z + row + e));
+            const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f_elem *>(z + row + e));
             zz[e] = v.x; zz[e + 1] = v.y; zz[e + 2] = v.z; zz[e + 3] = v.w;
         }
     }
@@ -189,10 +193,7 @@ __global__ __launch_bounds__(64) void coef_kernel(
 int launch_gemv_t(const void *grads, int dtype, const float *z, int64_t n, int m,
                   int64_t ld, Workspace *ws, double *w, hipStream_t stream)
 {
-    const size_t esz = dtype == QN_F32 ? 4 : 2;
-    const bool vec = (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
-                     (reinterpret_cast<uintptr_t>(z) % 16 == 0) &&
-                     ((static_cast<uint64_t>(ld) * esz) % 16 == 0);
+    const bool vec = n >= (dtype == QN_F32 ? 4 : 8);   // wide loads need no more than element alignment
     const int rows_per_thread = vec ? (dtype == QN_F32 ? 4 : 8) : 1;
     const int64_t per_block = static_cast<int64_t>(kGemvThreads) * rows_per_thread;
     const int64_t want = (n + per_block - 1) / per_block;
