@@ -35,7 +35,7 @@
  *   NULL is the default stream) and the call returns without synchronising.
  *   j_out is written on the device; synchronise the stream before reading it.
  * Workspace: the first call on a device allocates a fixed workspace (about
- *   13 MB) with hipMalloc and keeps it until qn_shutdown(); later calls
+ *   22 MB) with hipMalloc and keeps it until qn_shutdown(); later calls
  *   allocate nothing.  Calls on the same device share it: two calls that may
  *   overlap in time (different streams or host threads) race and must be
  *   serialised by the caller.
@@ -65,7 +65,7 @@
 extern "C" {
 #endif
 
-#define QN_MAX_M 32
+#define QN_MAX_M 64
 
 typedef enum {
     QN_OK = 0,

@@ -30,7 +30,8 @@ int get_workspace(Workspace **out)
             return QN_ELAUNCH;
         if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
             return QN_EARCH;
-        if (setup_gram_kernels() != QN_OK || setup_apply_kernels() != QN_OK)
+        if (setup_gram_kernels() != QN_OK || setup_apply_kernels() != QN_OK ||
+            setup_eig_kernels() != QN_OK)
             return QN_ELAUNCH;
         Workspace ws{};
         ws.cu_count = prop.multiProcessorCount;

@@ -321,6 +321,7 @@ static void launch_dt(ApplyShape shape, int grid, const void *thetas, const void
     case 8: launch_mc<DT, 8>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
     case 16: launch_mc<DT, 16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
     case 32: launch_mc<DT, 32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 64: launch_mc<DT, 64>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
     default: launch_mc<DT, 0>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
     }
 }
@@ -334,9 +335,9 @@ int setup_apply_kernels()
                                    hipFuncAttributeMaxDynamicSharedMemorySize,        \
                                    kStagedLdsBytes) == hipSuccess
     QN_OPT_IN(QN_F32, 0); QN_OPT_IN(QN_F32, 4); QN_OPT_IN(QN_F32, 8);
-    QN_OPT_IN(QN_F32, 16); QN_OPT_IN(QN_F32, 32);
+    QN_OPT_IN(QN_F32, 16); QN_OPT_IN(QN_F32, 32); QN_OPT_IN(QN_F32, 64);
     QN_OPT_IN(QN_BF16, 0); QN_OPT_IN(QN_BF16, 4); QN_OPT_IN(QN_BF16, 8);
-    QN_OPT_IN(QN_BF16, 16); QN_OPT_IN(QN_BF16, 32);
+    QN_OPT_IN(QN_BF16, 16); QN_OPT_IN(QN_BF16, 32); QN_OPT_IN(QN_BF16, 64);
 #undef QN_OPT_IN
     return ok ? QN_OK : QN_ELAUNCH;
 }

@@ -3,7 +3,8 @@
 //
 // One workgroup, everything in LDS, fp64 throughout.  The solver is the
 // parallel-order two-sided Jacobi method.  The matrix is padded to M = 2, 4, 8,
-// 16 or 32 (inert zero rows/columns).  The M indices are paired by a
+// 16, 24, 32, 48 or 64 (inert zero rows/columns); the block has 256 threads up
+// to M = 32 and 1024 above.  The M indices are paired by a
 // round-robin tournament: M/2 disjoint pairs per round, M-1 rounds per sweep,
 // the schedule tabulated once in LDS.  One round costs one barrier:
 //   * every wavefront computes all M/2 plane rotations redundantly (lane l owns
@@ -20,15 +21,18 @@
 
 namespace qn {
 
-constexpr int kEigThreads = 256;
 constexpr int kEigMaxSweeps = 30;
+template <int M> constexpr int eig_threads() { return M <= 32 ? 256 : 1024; }   // >= (M/2)^2, a power of two
+// dynamic LDS: two copies of the matrix and the eigenvectors, leading dimension M + 1
+template <int M> constexpr int eig_lds_bytes() { return 3 * M * (M + 1) * static_cast<int>(sizeof(double)); }
 
+template <int THREADS>
 __device__ __forceinline__ double block_sum(double v, double *scratch)
 {
     // fixed-order tree over the workgroup
     scratch[threadIdx.x] = v;
     __syncthreads();
-    for (int s = kEigThreads / 2; s > 0; s >>= 1) {
+    for (int s = THREADS / 2; s > 0; s >>= 1) {
         if (threadIdx.x < s)
             scratch[threadIdx.x] += scratch[threadIdx.x + s];
         __syncthreads();
@@ -38,11 +42,12 @@ __device__ __forceinline__ double block_sum(double v, double *scratch)
     return r;
 }
 
+template <int THREADS>
 __device__ __forceinline__ double block_max(double v, double *scratch)
 {
     scratch[threadIdx.x] = v;
     __syncthreads();
-    for (int s = kEigThreads / 2; s > 0; s >>= 1) {
+    for (int s = THREADS / 2; s > 0; s >>= 1) {
         if (threadIdx.x < s)
             scratch[threadIdx.x] = fmax(scratch[threadIdx.x], scratch[threadIdx.x + s]);
         __syncthreads();
@@ -94,7 +99,7 @@ __device__ __forceinline__ void rotation(double app, double aqq, double apq,
 }
 
 template <int M>
-__global__ __launch_bounds__(kEigThreads) void eig_select(
+__global__ __launch_bounds__(eig_threads<M>()) void eig_select(
     const double *__restrict__ C, const double *__restrict__ w, int m,
     double lambda, double *__restrict__ sigma_out, double *__restrict__ V_out,
     float *__restrict__ c_out, int *__restrict__ j_out)
@@ -102,8 +107,11 @@ __global__ __launch_bounds__(kEigThreads) void eig_select(
     constexpr int NP = M / 2;          // pairs per round
     constexpr int ROUNDS = M - 1;
     constexpr int LD = M + 1;          // padded leading dimension in LDS
-    __shared__ double A[2][M][LD];
-    __shared__ double V[M][LD];        // V[k][r]: component r of column k
+    constexpr int kEigThreads = eig_threads<M>();
+    extern __shared__ __attribute__((aligned(16))) double eig_lds[];
+    double (*A)[M][LD] = reinterpret_cast<double (*)[M][LD]>(eig_lds);   // A[2][M][LD]
+    double (*V)[LD] = reinterpret_cast<double (*)[LD]>(eig_lds + 2 * M * LD);
+    // V[k][r]: component r of column k
     __shared__ double scratch[kEigThreads];
     __shared__ unsigned char sp[ROUNDS][NP], sq[ROUNDS][NP];
     __shared__ double wv[M], sig[M], coef[M], cvec[M];
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_select(
     }
 
     // scale by a power of two so that the largest entry lies in [1, 2)
-    amax = block_max(amax, scratch);
+    amax = block_max<kEigThreads>(amax, scratch);
     int expo = 0;
     if (amax > 0.0)
         (void)frexp(amax, &expo);
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_select(
         A[0][e / M][e % M] = v;
         tot += v * v;
     }
-    const double tol2 = 1e-28 * block_sum(tot, scratch);
+    const double tol2 = 1e-28 * block_sum<kEigThreads>(tot, scratch);
 
     int cur = 0;
     const bool active = tid < NP * NP;
@@ -189,7 +197,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_select(
             if (k != l)
                 off += A[cur][k][l] * A[cur][k][l];
         }
-        if (block_sum(off, scratch) <= tol2)
+        if (block_sum<kEigThreads>(off, scratch) <= tol2)
             break;
 
         for (int round = 0; round < ROUNDS; ++round) {
@@ -304,15 +312,28 @@ int launch_eig(const double *C, const double *w, int m, float lambda,
     TraceScope ts(QN_K_EIG, stream);
     const double lam = static_cast<double>(lambda);
 #define QN_EIG_LAUNCH(MM)                                                            \
-    hipLaunchKernelGGL(eig_select<MM>, dim3(1), dim3(kEigThreads), 0, stream, C, w, \
-                       m, lam, sigma, V, c, j_out)
+    hipLaunchKernelGGL(eig_select<MM>, dim3(1), dim3(eig_threads<MM>()),             \
+                       eig_lds_bytes<MM>(), stream, C, w, m, lam, sigma, V, c, j_out)
     if (m <= 2) QN_EIG_LAUNCH(2);
     else if (m <= 4) QN_EIG_LAUNCH(4);
     else if (m <= 8) QN_EIG_LAUNCH(8);
     else if (m <= 16) QN_EIG_LAUNCH(16);
-    else QN_EIG_LAUNCH(32);
+    else if (m <= 24) QN_EIG_LAUNCH(24);
+    else if (m <= 32) QN_EIG_LAUNCH(32);
+    else if (m <= 48) QN_EIG_LAUNCH(48);
+    else QN_EIG_LAUNCH(64);
 #undef QN_EIG_LAUNCH
     return check_launch();
+}
+
+// The M = 64 instance keeps 98 KiB of matrices in dynamic LDS: per-device opt-in.
+int setup_eig_kernels()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(eig_select<64>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               eig_lds_bytes<64>()) == hipSuccess
+               ? QN_OK
+               : QN_ELAUNCH;
 }
 
 }  // namespace qn

@@ -18,7 +18,8 @@
 //   product the A and B operands are the same register: lane l of a wavefront
 //   supplies column l%16 (and l%16 + 16 when m > 16) for the row slot l/16, and
 //   any assignment of rows to the four slots is valid as long as both operands
-//   agree.  Only the lower triangle of the 2x2 tiling is computed (3 of 4
+//   agree.  The m columns form NT = 1..4 sets of 16 (m <= 16, 32, 48, 64) and
+//   only the lower triangle of the NT x NT tiling is computed (1, 3, 6 or 10
 //   tiles).  MFMA accumulators run in fp32 over one tile and are then added to
 //   per-lane fp64 totals; waves are combined through LDS in a fixed order and
 //   each block writes one partial.  No atomics.
@@ -43,59 +44,30 @@ namespace qn {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 
 #define QN_GPTR(p) ((const __attribute__((address_space(1))) void *)(p))
 #define QN_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
-template <int NT> struct GramTiles { static constexpr int value = (NT == 1) ? 1 : 3; };
-
-// Combines the per-lane fp64 totals of the block's wavefronts in wave order
-// and writes the block's partial.  `red` must hold kGramWaves*TILES*4*64 doubles.
-template <int TILES>
-__device__ __forceinline__ void write_block_partial(const double (&tot)[TILES][4],
-                                                    double *red, double *partials)
-{
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int t = 0; t < TILES; ++t)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            red[(wave * TILES * 4 + t * 4 + r) * 64 + lane] = tot[t][r];
-    __syncthreads();
-    constexpr int ENTRIES = TILES * kTileEntries;
-    for (int e = threadIdx.x; e < ENTRIES; e += kGramThreads) {
-        double s = 0.0;
-#pragma unroll
-        for (int wv = 0; wv < kGramWaves; ++wv)
-            s += red[wv * ENTRIES + e];
-        partials[static_cast<int64_t>(blockIdx.x) * ENTRIES + e] = s;
-    }
-}
-
-// One MFMA k-step for the three lower-triangle tiles (or the single tile).
-template <int NT>
-__device__ __forceinline__ void gram_step(float da, float db, v4f (&acc)[GramTiles<NT>::value])
-{
-    acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(da, da, acc[0], 0, 0, 0);
-    if constexpr (NT == 2) {
-        acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(db, da, acc[1], 0, 0, 0);
-        acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(db, db, acc[2], 0, 0, 0);
-    }
-}
+// NT column sets of 16: lower-triangle tiles, tile (ti, tj), ti >= tj, at index
+// ti (ti + 1) / 2 + tj.
+template <int NT> struct GramTiles { static constexpr int value = NT * (NT + 1) / 2; };
+__host__ __device__ constexpr int tile_index(int ti, int tj) { return ti * (ti + 1) / 2 + tj; }
 
 // ---------------------------------------------------------------------------
-// Fast path.  Tile = kStreamRows rows of all columns; a column's rows of one tile
-// are 1 KiB of contiguous memory (256 fp32 or 512 bf16 rows) and land in LDS at
-// column * kColPitch (1 KiB + 16 B, which spreads the 16 columns a quarter-wave
-// reads over all banks).
+// A tile is ROWS rows of all columns; a column's rows of one tile are 1 KiB in
+// LDS at slot * kColPitch (1 KiB + 16 B, which spreads the 16 columns a
+// quarter-wave reads over all banks).  16 * NT slots per stage, two stages.
 constexpr int kColPitch = 1040;                       // bytes per column slot
-constexpr int kStageBytes = QN_MAX_M * kColPitch;     // 33 280
-constexpr int kStreamLdsBytes = 2 * kStageBytes;      // two stages
+template <int NT> constexpr int stage_bytes() { return 16 * NT * kColPitch; }
+template <int NT> constexpr int stream_lds_bytes() { return 2 * stage_bytes<NT>(); }
+// blocks per CU that fit the 160 KiB of LDS (and 32 waves): 4, 2, 1, 1
+template <int NT> constexpr int stream_blocks_per_cu() { return NT == 1 ? 4 : (NT == 2 ? 2 : 1); }
 
-// Rows per tile: a column's tile is 1 KiB in LDS.  bf16 inputs that are not
-// 16-byte aligned arrive through 2-byte direct-to-LDS loads, which the hardware
-// stores zero-extended, one per dword: their LDS format is 4 bytes per row.
+// Rows per tile.  bf16 inputs that are not 16-byte aligned arrive through
+// 2-byte direct-to-LDS loads, which the hardware stores zero-extended, one per
+// dword: their LDS format is 4 bytes per row.
 template <int DT, bool ALIGNED> struct StreamRows {
     static constexpr int value = (DT == QN_F32 || !ALIGNED) ? 256 : 512;
 };
@@ -123,16 +95,14 @@ __device__ __forceinline__ void lds_rows(const char *p, float (&x)[FMT == 1 ? 8 
     }
 }
 
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-
-// d = present ? (keep_raw ? x : x - s) : 0, split into bf16 hi + lo (see the caller).
-template <int N>
-__device__ __forceinline__ void split_bf16(const float (&x)[N], const float (&s)[N],
+// d = present ? (keep_raw ? x : x - s) : 0 for 8 rows, split into bf16 hi + lo:
+// hi = the upper 16 bits of d, lo = bf16(d - hi).  Exact whenever d has at most
+// 16 significant bits (always, unless x and s differ by more than 2^8 in
+// magnitude), else good to 2^-16.
+__device__ __forceinline__ void split_bf16(const float (&x)[8], const float (&s)[8],
                                            bool present, bool keep_raw, v8bf &hi,
                                            v8bf &lo)
 {
-    static_assert(N == 8, "one K-slice is 8 rows");
     uint32_t hw[4], lw[4];
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
@@ -148,30 +118,6 @@ __device__ __forceinline__ void split_bf16(const float (&x)[N], const float (&s)
     const v4u hv = {hw[0], hw[1], hw[2], hw[3]}, lv = {lw[0], lw[1], lw[2], lw[3]};
     hi = __builtin_bit_cast(v8bf, hv);
     lo = __builtin_bit_cast(v8bf, lv);
-}
-
-// One K = 32 step of the lower-triangle tiles on the bf16 matrix cores:
-// (hi + lo)(hi + lo)^T expanded into its four products.
-template <int NT>
-__device__ __forceinline__ void gram_step_bf16(v8bf ahi, v8bf alo, v8bf bhi, v8bf blo,
-                                               v4f (&acc)[GramTiles<NT>::value])
-{
-#define QN_MFMA_BF16(A, B, C) C = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
-    QN_MFMA_BF16(ahi, ahi, acc[0]);
-    QN_MFMA_BF16(ahi, alo, acc[0]);
-    QN_MFMA_BF16(alo, ahi, acc[0]);
-    QN_MFMA_BF16(alo, alo, acc[0]);
-    if constexpr (NT == 2) {
-        QN_MFMA_BF16(bhi, ahi, acc[1]);
-        QN_MFMA_BF16(bhi, alo, acc[1]);
-        QN_MFMA_BF16(blo, ahi, acc[1]);
-        QN_MFMA_BF16(blo, alo, acc[1]);
-        QN_MFMA_BF16(bhi, bhi, acc[2]);
-        QN_MFMA_BF16(bhi, blo, acc[2]);
-        QN_MFMA_BF16(blo, bhi, acc[2]);
-        QN_MFMA_BF16(blo, blo, acc[2]);
-    }
-#undef QN_MFMA_BF16
 }
 
 // ALIGNED: every column start is 16-byte aligned, one 128-bit load per lane moves
@@ -190,17 +136,20 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     constexpr int LESZ = WIDE ? 4 : ESZ;                 // element size in LDS
     constexpr int FMT = DT == QN_F32 ? 0 : (WIDE ? 2 : 1);
     constexpr int RPV = 16 / LESZ;                       // rows per 16-byte LDS vector
-    constexpr int COLS_PER_WAVE = QN_MAX_M / kGramWaves; // columns a wave loads
-    constexpr int VEC_PER_GROUP = ROWS / kGramWaves / 4 / RPV;   // 2 either way
+    constexpr int SLOTS_PER_WAVE = 16 * NT / kGramWaves; // column slots a wave loads
+    constexpr int VEC_PER_GROUP = ROWS / kGramWaves / 4 / RPV;   // 2 in every format
+    constexpr int STAGE = stage_bytes<NT>();
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int col = lane & 15;
     const int group = lane >> 4;
-    const bool has_a = col < m;
-    const bool has_b = (NT == 2) && (col + 16 < m);
     const bool is_pivot = col == 0;
+    bool has[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+        has[t] = col + 16 * t < m;
     const char *base = static_cast<const char *>(grads);
 
     const int64_t num_tiles = (n + ROWS - 1) / ROWS;
@@ -210,11 +159,11 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     auto fetch = [&](int64_t k) {
         const int64_t tile = blockIdx.x + k * gridDim.x;
         const int64_t row0 = tile * ROWS;
-        char *stage = lds + (k & 1) * kStageBytes;
+        char *stage = lds + (k & 1) * STAGE;
         if (row0 + ROWS <= n) {
 #pragma unroll
-            for (int jc = 0; jc < COLS_PER_WAVE; ++jc) {
-                const int c = wave * COLS_PER_WAVE + jc;
+            for (int jc = 0; jc < SLOTS_PER_WAVE; ++jc) {
+                const int c = wave * SLOTS_PER_WAVE + jc;
                 if (c < m) {
                     const char *g = base + (static_cast<int64_t>(c) * ld + row0) * ESZ;
                     if constexpr (ALIGNED) {
@@ -236,8 +185,8 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
             }
         } else {
             // the ragged last tile: guarded element loads, zero fill
-            for (int jc = 0; jc < COLS_PER_WAVE; ++jc) {
-                const int c = wave * COLS_PER_WAVE + jc;
+            for (int jc = 0; jc < SLOTS_PER_WAVE; ++jc) {
+                const int c = wave * SLOTS_PER_WAVE + jc;
                 if (c >= m)
                     continue;
                 for (int e = 0; e < RPV; ++e) {
@@ -277,7 +226,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
         if (k + 1 < mine)
             fetch(k + 1);
 
-        const char *stage = lds + (k & 1) * kStageBytes;
+        const char *stage = lds + (k & 1) * STAGE;
         // this wave's rows: its share of the tile; this lane group's: a quarter of that
         const int byte0 = (wave * (ROWS / kGramWaves) + group * (ROWS / kGramWaves / 4)) * LESZ;
         v4f acc[TILES];
@@ -286,32 +235,44 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
             acc[t] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int i = 0; i < VEC_PER_GROUP; ++i) {
-            float a[RPV], b[RPV], s[RPV];
-            lds_rows<FMT>(stage + col * kColPitch + byte0 + 16 * i, a);
+            float x[NT][RPV], s[RPV];
             lds_rows<FMT>(stage + byte0 + 16 * i, s);            // column 0: the pivot
-            if constexpr (NT == 2)
-                lds_rows<FMT>(stage + (col + 16) * kColPitch + byte0 + 16 * i, b);
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                lds_rows<FMT>(stage + (col + 16 * t) * kColPitch + byte0 + 16 * i, x[t]);
             if constexpr (FMT != 1) {
+                // fp32 matrix cores: one k-step of 4 rows per element of the vector
 #pragma unroll
                 for (int e = 0; e < RPV; ++e) {
-                    const float da = has_a ? (is_pivot ? a[e] : a[e] - s[e]) : 0.0f;
-                    float db = 0.0f;
-                    if constexpr (NT == 2)
-                        db = has_b ? b[e] - s[e] : 0.0f;
-                    gram_step<NT>(da, db, acc);
+                    float d[NT];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        d[t] = has[t] ? ((t == 0 && is_pivot) ? x[t][e] : x[t][e] - s[e]) : 0.0f;
+#pragma unroll
+                    for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+                        for (int tj = 0; tj <= ti; ++tj)
+                            acc[tile_index(ti, tj)] = __builtin_amdgcn_mfma_f32_16x16x4f32(
+                                d[ti], d[tj], acc[tile_index(ti, tj)], 0, 0, 0);
                 }
             } else {
                 // bf16 storage: the 8 rows a lane just read are one K-slice of
-                // v_mfma_f32_16x16x32_bf16.  The shifted value d = x - s (exact in
-                // fp32) is split as hi + lo, hi = its upper 16 bits (a bf16), lo =
-                // bf16(d - hi): exact whenever d has at most 16 significant bits
-                // (always, unless x and s differ by more than 2^8 in magnitude),
-                // else good to 2^-16.  All four hi/lo products are accumulated.
-                v8bf ahi, alo, bhi = {}, blo = {};
-                split_bf16<RPV>(a, s, has_a, is_pivot, ahi, alo);
-                if constexpr (NT == 2)
-                    split_bf16<RPV>(b, s, has_b, false, bhi, blo);
-                gram_step_bf16<NT>(ahi, alo, bhi, blo, acc);
+                // v_mfma_f32_16x16x32_bf16; (hi + lo)(hi + lo)^T is expanded into
+                // its four products
+                v8bf hi[NT], lo[NT];
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    split_bf16(x[t], s, has[t], t == 0 && is_pivot, hi[t], lo[t]);
+#pragma unroll
+                for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+                    for (int tj = 0; tj <= ti; ++tj) {
+                        v4f &a = acc[tile_index(ti, tj)];
+                        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], hi[tj], a, 0, 0, 0);
+                        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], lo[tj], a, 0, 0, 0);
+                        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo[ti], hi[tj], a, 0, 0, 0);
+                        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo[ti], lo[tj], a, 0, 0, 0);
+                    }
             }
         }
 #pragma unroll
@@ -321,7 +282,35 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
                 tot[t][r] += static_cast<double>(acc[t][r]);
     }
     __syncthreads();   // all reads of the stages are done: reuse them for the reduction
-    write_block_partial<TILES>(tot, reinterpret_cast<double *>(lds), partials);
+
+    // Combine the wavefronts of the block in wave order, one tile at a time
+    // (256 entries of 8 waves = 16 KiB of the stage memory).
+    double *red = reinterpret_cast<double *>(lds);
+    constexpr int ENTRIES = TILES * kTileEntries;
+#pragma unroll 1
+    for (int t = 0; t < TILES; ++t) {
+        // tot[t] with a loop-variant t would live in scratch: select statically
+        double mine4[4];
+#pragma unroll
+        for (int tt = 0; tt < TILES; ++tt)
+            if (tt == t) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    mine4[r] = tot[tt][r];
+            }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            red[(wave * 4 + r) * 64 + lane] = mine4[r];
+        __syncthreads();
+        if (threadIdx.x < kTileEntries) {
+            double sum = 0.0;
+#pragma unroll
+            for (int wv = 0; wv < kGramWaves; ++wv)
+                sum += red[wv * kTileEntries + threadIdx.x];
+            partials[static_cast<int64_t>(blockIdx.x) * ENTRIES + t * kTileEntries + threadIdx.x] = sum;
+        }
+        __syncthreads();
+    }
 }
 
 // Fixed-order fp64 sum over the block partials.  Block b owns 64 entries; 16
@@ -364,33 +353,34 @@ __global__ __launch_bounds__(64 * kReduceSlices) void gram_reduce(
 // of lane 16*(i/4) + j.
 __device__ __forceinline__ int raw_index(int k, int l)
 {
-    const int ti = k >> 4, tj = l >> 4;
-    const int tile = ti + tj;              // (0,0)->0, (1,0)->1, (1,1)->2
+    const int tile = tile_index(k >> 4, l >> 4);
     const int i = k & 15, j = l & 15;
     return (tile * 4 + (i & 3)) * 64 + (i >> 2) * 16 + j;
 }
 
-// C = P N P and w = P (t + N 1 / m) in fp64; one block of QN_MAX_M^2 threads.
-__global__ __launch_bounds__(QN_MAX_M *QN_MAX_M) void gram_project(
+// C = P N P and w = P (t + N 1 / m) in fp64; one block.
+constexpr int kProjectThreads = 1024;
+__global__ __launch_bounds__(kProjectThreads) void gram_project(
     const double *__restrict__ mraw, int m, double *__restrict__ C,
     double *__restrict__ w)
 {
     __shared__ double N[QN_MAX_M][QN_MAX_M + 1];
     __shared__ double rowsum[QN_MAX_M], u[QN_MAX_M];
     __shared__ double total, umean;
-    const int k = threadIdx.x / QN_MAX_M, l = threadIdx.x % QN_MAX_M;
-    double q = 0.0;
-    if (k < m && l < m && k >= 1 && l >= 1)
-        q = (k >= l) ? mraw[raw_index(k, l)] : mraw[raw_index(l, k)];
-    N[k][l] = q;
+    for (int e = threadIdx.x; e < m * m; e += kProjectThreads) {
+        const int k = e / m, l = e % m;
+        double q = 0.0;
+        if (k >= 1 && l >= 1)
+            q = (k >= l) ? mraw[raw_index(k, l)] : mraw[raw_index(l, k)];
+        N[k][l] = q;
+    }
     __syncthreads();
-    if (threadIdx.x < QN_MAX_M) {
+    if (threadIdx.x < m) {
         double s = 0.0;
         for (int x = 0; x < m; ++x)
             s += N[threadIdx.x][x];
         rowsum[threadIdx.x] = s;
-        const double t = (threadIdx.x >= 1 && threadIdx.x < m)
-                             ? mraw[raw_index(threadIdx.x, 0)] : 0.0;
+        const double t = threadIdx.x >= 1 ? mraw[raw_index(threadIdx.x, 0)] : 0.0;
         u[threadIdx.x] = t + s / m;
     }
     __syncthreads();
@@ -404,8 +394,10 @@ __global__ __launch_bounds__(QN_MAX_M *QN_MAX_M) void gram_project(
         umean = su / m;
     }
     __syncthreads();
-    if (k < m && l < m)
+    for (int e = threadIdx.x; e < m * m; e += kProjectThreads) {
+        const int k = e / m, l = e % m;
         C[l * m + k] = N[k][l] - (rowsum[k] + rowsum[l]) / m + total / (static_cast<double>(m) * m);
+    }
     if (threadIdx.x < m)
         w[threadIdx.x] = u[threadIdx.x] - umean;
 }
@@ -416,34 +408,49 @@ static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t 
 {
     const int rows = aligned ? StreamRows<DT, true>::value : StreamRows<DT, false>::value;
     const int64_t num_tiles = (n + rows - 1) / rows;
-    const int64_t cap = static_cast<int64_t>(cu_count) * 2;   // two 65 KB blocks per CU
+    const int64_t cap = static_cast<int64_t>(cu_count) * stream_blocks_per_cu<NT>();
     const int grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
     if (aligned)
         hipLaunchKernelGGL((gram_stage1_stream<DT, NT, true>), dim3(grid), dim3(kGramThreads),
-                           kStreamLdsBytes, stream, grads, n, m, ld, partials);
+                           stream_lds_bytes<NT>(), stream, grads, n, m, ld, partials);
     else
         hipLaunchKernelGGL((gram_stage1_stream<DT, NT, false>), dim3(grid), dim3(kGramThreads),
-                           kStreamLdsBytes, stream, grads, n, m, ld, partials);
+                           stream_lds_bytes<NT>(), stream, grads, n, m, ld, partials);
     return grid;
 }
 
-// The streaming kernels use more than the default 64 KiB of dynamic LDS; the
-// opt-in is per device and is made once when the device's workspace is set up.
+template <int DT>
+static int launch_stage1_nt(int nt, bool aligned, int cu_count, const void *grads,
+                            int64_t n, int m, int64_t ld, double *partials,
+                            hipStream_t stream)
+{
+    if (nt == 1)
+        return launch_stage1<DT, 1>(aligned, cu_count, grads, n, m, ld, partials, stream);
+    if (nt == 2)
+        return launch_stage1<DT, 2>(aligned, cu_count, grads, n, m, ld, partials, stream);
+    if (nt == 3)
+        return launch_stage1<DT, 3>(aligned, cu_count, grads, n, m, ld, partials, stream);
+    return launch_stage1<DT, 4>(aligned, cu_count, grads, n, m, ld, partials, stream);
+}
+
+// The streaming kernels use up to 130 KiB of dynamic LDS; the opt-in above the
+// default 64 KiB is per device and is made once when the device's workspace is
+// set up.
 int setup_gram_kernels()
 {
     bool ok = true;
-#define QN_OPT_IN(K)                                                                   \
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(K),                  \
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,        \
-                                   kStreamLdsBytes) == hipSuccess
-    QN_OPT_IN((gram_stage1_stream<QN_F32, 1, true>));
-    QN_OPT_IN((gram_stage1_stream<QN_F32, 2, true>));
-    QN_OPT_IN((gram_stage1_stream<QN_BF16, 1, true>));
-    QN_OPT_IN((gram_stage1_stream<QN_BF16, 2, true>));
-    QN_OPT_IN((gram_stage1_stream<QN_F32, 1, false>));
-    QN_OPT_IN((gram_stage1_stream<QN_F32, 2, false>));
-    QN_OPT_IN((gram_stage1_stream<QN_BF16, 1, false>));
-    QN_OPT_IN((gram_stage1_stream<QN_BF16, 2, false>));
+#define QN_OPT_IN(DTV, NTV, AL)                                                            \
+    ok = ok && hipFuncSetAttribute(                                                        \
+                   reinterpret_cast<const void *>(gram_stage1_stream<DTV, NTV, AL>),       \
+                   hipFuncAttributeMaxDynamicSharedMemorySize,                             \
+                   stream_lds_bytes<NTV>()) == hipSuccess
+#define QN_OPT_IN_ALL(DTV)                                                                 \
+    QN_OPT_IN(DTV, 1, true); QN_OPT_IN(DTV, 1, false); QN_OPT_IN(DTV, 2, true);            \
+    QN_OPT_IN(DTV, 2, false); QN_OPT_IN(DTV, 3, true); QN_OPT_IN(DTV, 3, false);          \
+    QN_OPT_IN(DTV, 4, true); QN_OPT_IN(DTV, 4, false)
+    QN_OPT_IN_ALL(QN_F32);
+    QN_OPT_IN_ALL(QN_BF16);
+#undef QN_OPT_IN_ALL
 #undef QN_OPT_IN
     return ok ? QN_OK : QN_ELAUNCH;
 }
@@ -454,20 +461,17 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     const size_t esz = dtype == QN_F32 ? 4 : 2;
     const bool aligned = (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
                          ((static_cast<uint64_t>(ld) * esz) % 16 == 0);
-    const int nt = m <= 16 ? 1 : 2;
-    const int entries = (nt == 1 ? 1 : 3) * kTileEntries;
+    const int nt = (m + 15) / 16;
+    const int entries = nt * (nt + 1) / 2 * kTileEntries;
 
-    // the grid is a function of (n, dtype, alignment) and the device's CU count
-    // only, so the summation tree is reproducible
+    // the grid is a function of (n, m, dtype, alignment) and the device's CU
+    // count only, so the summation tree is reproducible
     int grid;
     {
         TraceScope ts(QN_K_GRAM, stream);
-        if (dtype == QN_F32)
-            grid = nt == 1 ? launch_stage1<QN_F32, 1>(aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream)
-                           : launch_stage1<QN_F32, 2>(aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream);
-        else
-            grid = nt == 1 ? launch_stage1<QN_BF16, 1>(aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream)
-                           : launch_stage1<QN_BF16, 2>(aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream);
+        grid = dtype == QN_F32
+                   ? launch_stage1_nt<QN_F32>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream)
+                   : launch_stage1_nt<QN_BF16>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream);
     }
     if (grid < 0 || grid > kGramMaxBlocks)
         return QN_ELAUNCH;
@@ -480,7 +484,7 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     if (check_launch() != QN_OK) return QN_ELAUNCH;
     {
         TraceScope ts(QN_K_PROJECT, stream);
-        hipLaunchKernelGGL(gram_project, dim3(1), dim3(QN_MAX_M * QN_MAX_M), 0, stream,
+        hipLaunchKernelGGL(gram_project, dim3(1), dim3(kProjectThreads), 0, stream,
                            ws->mraw, m, C, w);
     }
     return check_launch();

@@ -125,21 +125,22 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_t_kernel(
 
 // Sums the block partials in block order and applies the centring projector:
 // w = u - mean(u) over the m workers (u_0 = 0: the pivot column of D is zero).
-__global__ __launch_bounds__(QN_MAX_M *32) void gemv_finish(
+constexpr int kFinishSlices = 1024 / QN_MAX_M;
+__global__ __launch_bounds__(QN_MAX_M * kFinishSlices) void gemv_finish(
     const double *__restrict__ partials, int num_partials, int m,
     double *__restrict__ w)
 {
-    __shared__ double part[32][QN_MAX_M];
+    __shared__ double part[kFinishSlices][QN_MAX_M];
     __shared__ double u[QN_MAX_M];
     const int k = threadIdx.x % QN_MAX_M, slice = threadIdx.x / QN_MAX_M;
     double s = 0.0;
-    for (int p = slice; p < num_partials; p += 32)
+    for (int p = slice; p < num_partials; p += kFinishSlices)
         s += partials[static_cast<int64_t>(p) * QN_MAX_M + k];
     part[slice][k] = s;
     __syncthreads();
     if (threadIdx.x < QN_MAX_M) {
         double r = 0.0;
-        for (int sl = 0; sl < 32; ++sl)
+        for (int sl = 0; sl < kFinishSlices; ++sl)
             r += part[sl][threadIdx.x];
         u[threadIdx.x] = threadIdx.x < m ? r : 0.0;
     }
@@ -217,7 +218,7 @@ int launch_gemv_t(const void *grads, int dtype, const float *z, int64_t n, int m
         return QN_ELAUNCH;
     {
         TraceScope ts(QN_K_GEMV, stream);
-        hipLaunchKernelGGL(gemv_finish, dim3(1), dim3(QN_MAX_M * 32), 0, stream,
+        hipLaunchKernelGGL(gemv_finish, dim3(1), dim3(QN_MAX_M * kFinishSlices), 0, stream,
                            ws->gemv_partials, grid, m, w);
     }
     return check_launch();

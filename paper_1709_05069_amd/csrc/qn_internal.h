@@ -12,16 +12,16 @@ namespace qn {
 // ---- fixed launch geometry -------------------------------------------------
 // The Gram pass runs a fixed grid so that the summation tree depends only on
 // (n, m, dtype).  Each block writes one partial; the partial holds the raw
-// MFMA accumulator layout: TILE_ENTRIES values per 16x16 tile, up to 3 tiles
-// (the lower triangle of a 2x2 tiling of a 32x32 matrix).
+// MFMA accumulator layout: kTileEntries values per 16x16 tile, 1, 3, 6 or 10
+// tiles (the lower triangle of a 1x1 .. 4x4 tiling: m <= 16, 32, 48, 64).
 #ifndef QN_GRAM_THREADS
 #define QN_GRAM_THREADS 512                     // 8 wavefronts
 #endif
 constexpr int kGramThreads = QN_GRAM_THREADS;
 constexpr int kGramWaves = kGramThreads / 64;
-constexpr int kGramMaxBlocks = 2048;
+constexpr int kGramMaxBlocks = 1024;
 constexpr int kTileEntries = 256;               // 16 x 16
-constexpr int kMaxTiles = 3;
+constexpr int kMaxTiles = 10;                   // lower triangle of a 4x4 tiling (m <= 64)
 constexpr int kMaxEntries = kTileEntries * kMaxTiles;
 constexpr int kGemvMaxBlocks = 2048;
 
@@ -48,6 +48,7 @@ int get_workspace(Workspace **out);
 // ---- per-device kernel set-up (called once when a device's workspace is made) --
 int setup_gram_kernels();
 int setup_apply_kernels();
+int setup_eig_kernels();
 
 // ---- kernel launchers (each enqueues on `stream`, returns a qn_status) ------
 int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,

@@ -59,7 +59,7 @@ def test_argument_errors_are_reported_before_any_device_work(lib):
     p = 0x1000
     assert lib.qn_update(p, p, 0, 4, 1.0, 0.1, p, p, None) == -1        # n < 1
     assert lib.qn_update(p, p, 10, 0, 1.0, 0.1, p, p, None) == -1       # m < 1
-    assert lib.qn_update(p, p, 10, 33, 1.0, 0.1, p, p, None) == -1      # m > max
+    assert lib.qn_update(p, p, 10, 65, 1.0, 0.1, p, p, None) == -1      # m > max
     assert lib.qn_update(p, p, 10, 4, float("nan"), 0.1, p, p, None) == -1
     assert lib.qn_update(p, p, 10, 4, 1.0, 0.0, p, p, None) == -1       # lambda <= 0
     assert lib.qn_update(p, p, 10, 4, 1.0, float("inf"), p, p, None) == -1

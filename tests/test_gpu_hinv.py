@@ -31,7 +31,8 @@ def oracle_pieces(th_np, gr_np, lam):
 CASES = [("tiny_exact", 4096, None, 0.01), ("small_mlp", 30_001, None, 0.05),
          ("resnet50", 50_000, None, 0.01), ("gpt2_small", 40_000, None, 0.01),
          ("gpt2_small", 9_999, 23, 0.01), ("stress_1b_bf16", 40_000, None, 0.02),
-         ("stress_1b_bf16", 12_345, 9, 0.02)]
+         ("stress_1b_bf16", 12_345, 9, 0.02), ("gpt2_small", 20_000, 64, 0.01),
+         ("stress_1b_bf16", 16_001, 40, 0.02)]
 
 
 @pytest.mark.parametrize("name,n,m,lam", CASES)

@@ -58,6 +58,9 @@ GRAM_CASES = [
     ("resnet50", 100003, 16), ("resnet50", 66001, 17), ("gpt2_small", 200000, 32),
     ("gpt2_small", 129, 32), ("gpt2_small", 50001, 31), ("stress_1b_bf16", 70000, 32),
     ("stress_1b_bf16", 4097, 8), ("stress_1b_bf16", 33333, 20),
+    # more than 32 workers: the 4x4 tiling
+    ("gpt2_small", 60000, 64), ("gpt2_small", 30001, 33), ("resnet50", 20480, 48),
+    ("stress_1b_bf16", 40000, 64), ("stress_1b_bf16", 20003, 47),
 ]
 
 
@@ -120,7 +123,8 @@ def _engineered_C(m, svals, seed):
 
 @pytest.mark.parametrize("m,lam", [(2, 0.5), (3, 0.3), (4, 0.5), (7, 0.2), (8, 0.6),
                                    (16, 0.35), (17, 0.9), (31, 0.05), (32, 0.5),
-                                   (32, 1e-3), (32, 1.5)])
+                                   (32, 1e-3), (32, 1.5), (24, 0.1), (25, 0.1), (33, 0.3), (40, 0.2), (48, 0.05), (49, 0.1),
+                                   (64, 0.5), (64, 1e-3)])
 def test_eig_select_matches_oracle_on_engineered_spectra(m, lam):
     svals = np.geomspace(1.0, 0.02, m - 1) * 3.7
     C, w = _engineered_C(m, svals, 40 + m)
@@ -169,6 +173,7 @@ APPLY_CASES = [
     ("small_mlp", 70001, 5), ("resnet50", 100000, 16), ("gpt2_small", 65537, 32),
     ("gpt2_small", 40000, 1), ("stress_1b_bf16", 50000, 32),
     ("stress_1b_bf16", 12345, 8), ("stress_1b_bf16", 8200, 23),
+    ("gpt2_small", 30000, 64), ("gpt2_small", 10001, 40), ("stress_1b_bf16", 16008, 64),
 ]
 
 
@@ -205,7 +210,8 @@ UPDATE_CASES = [
     ("small_mlp", 1_200_000, None),       # configs[1] at full size
     ("resnet50", 300_001, None), ("gpt2_small", 250_000, None),
     ("stress_1b_bf16", 200_000, None), ("small_mlp", 50_000, 3),
-    ("gpt2_small", 10_000, 27),
+    ("gpt2_small", 10_000, 27), ("gpt2_small", 50_000, 64), ("stress_1b_bf16", 30_000, 48),
+    ("resnet50", 20_000, 33),
 ]
 
 
