@@ -60,6 +60,12 @@ def load_library(path):
     L.qno_apply_closed_form.argtypes = [_vp, _vp, _int, _i64, _int, _i64,
                                         _vp, _dbl, _vp]
     L.qno_apply_closed_form.restype = None
+    L.qno_tau_bounded_literal.argtypes = [_dbl, _int, _vp, _vp, _i64, _int, _vp,
+                                          _vp, _int, _vp]
+    L.qno_tau_bounded_literal.restype = _dbl
+    L.qno_tau_bounded_from_gram.argtypes = [_dbl, _int, _vp, _int, _vp, _vp,
+                                            _int, _vp]
+    L.qno_tau_bounded_from_gram.restype = _dbl
     return L
 
 
@@ -264,3 +270,29 @@ def update_streaming(thetas, grads, tau: float, lam: float,
             T[:, r0:r0 + chunk_rows], Gr[:, r0:r0 + chunk_rows], co["c"], tau)
     return dict(theta_new=theta_new, j=co["j"], C=C, w=w, sigma=co["sigma"],
                 V=co["V"], c=co["c"], alpha=co["alpha"])
+
+
+BOUND_SIGMA1, BOUND_SECANT = 1, 2
+
+
+def tau_bounded_literal(tau: float, mode: int, Theta, G, sigma, V, j: int):
+    """(tau_eff, sigma_max) with the norms of G v_k, Theta v_k formed explicitly."""
+    Theta = _f64(Theta)
+    G = _f64(G)
+    m, n = G.shape
+    smax = ctypes.c_double(0.0)
+    t = lib().qno_tau_bounded_literal(float(tau), int(mode), _p(Theta), _p(G), n, m,
+                                      _p(_f64(sigma)), _p(_f64(V)), int(j),
+                                      ctypes.byref(smax))
+    return t, smax.value
+
+
+def tau_bounded_from_gram(tau: float, mode: int, Ct, sigma, V, j: int):
+    """(tau_eff, sigma_max) from Ct = Theta^T Theta and the eigendecomposition."""
+    Ct = _f64(Ct)
+    m = Ct.shape[0]
+    smax = ctypes.c_double(0.0)
+    t = lib().qno_tau_bounded_from_gram(float(tau), int(mode), _p(Ct), m,
+                                        _p(_f64(sigma)), _p(_f64(V)), int(j),
+                                        ctypes.byref(smax))
+    return t, smax.value

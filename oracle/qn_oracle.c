@@ -359,3 +359,72 @@ void qno_apply_closed_form(const void *thetas, const void *grads, int dtype,
         theta_new[i] = tbar - tau * (gbar + corr);
     }
 }
+
+/* ---- step size capped by 1 / sigma_max (Section 3, closing discussion) ---- */
+
+static double cap_tau(double tau, int have, double smax, double *sigma_max)
+{
+    if (sigma_max)
+        *sigma_max = have ? smax : 0.0;
+    if (!have)
+        return tau;
+    return fmin(tau, 1.0 / smax);
+}
+
+double qno_tau_bounded_literal(double tau, int mode, const double *Theta,
+                               const double *G, int64_t n, int m,
+                               const double *sigma, const double *V, int j,
+                               double *sigma_max)
+{
+    (void)sigma;
+    if (mode == QNO_BOUND_SIGMA1) {
+        /* sigma_1 = ||G v_1||_2, taken from the matrix itself */
+        double s2 = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            double gv = 0.0;
+            for (int r = 0; r < m; ++r)
+                gv += G[(int64_t)r * n + i] * V[r];
+            s2 += gv * gv;
+        }
+        return cap_tau(tau, s2 > 0.0, sqrt(s2), sigma_max);
+    }
+    double smax = 0.0;
+    for (int k = 0; k < j; ++k) {
+        double g2 = 0.0, y2 = 0.0;
+        for (int64_t i = 0; i < n; ++i) {
+            double gv = 0.0, yv = 0.0;
+            for (int r = 0; r < m; ++r) {
+                gv += G[(int64_t)r * n + i] * V[k * m + r];
+                yv += Theta[(int64_t)r * n + i] * V[k * m + r];
+            }
+            g2 += gv * gv;
+            y2 += yv * yv;
+        }
+        const double q = sqrt(g2) / sqrt(y2);   /* +inf when Theta v_k = 0 */
+        if (q > smax)
+            smax = q;
+    }
+    return cap_tau(tau, j > 0, smax, sigma_max);
+}
+
+double qno_tau_bounded_from_gram(double tau, int mode, const double *Ct, int m,
+                                 const double *sigma, const double *V, int j,
+                                 double *sigma_max)
+{
+    if (mode == QNO_BOUND_SIGMA1)
+        return cap_tau(tau, sigma[0] > 0.0, sigma[0], sigma_max);
+    double smax = 0.0;
+    for (int k = 0; k < j; ++k) {
+        double y2 = 0.0;
+        for (int r = 0; r < m; ++r) {
+            double row = 0.0;
+            for (int q = 0; q < m; ++q)
+                row += Ct[q * m + r] * V[k * m + q];
+            y2 += V[k * m + r] * row;
+        }
+        const double quot = sigma[k] / sqrt(y2 > 0.0 ? y2 : 0.0);
+        if (quot > smax)
+            smax = quot;
+    }
+    return cap_tau(tau, j > 0, smax, sigma_max);
+}

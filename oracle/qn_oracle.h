@@ -18,7 +18,9 @@
  * closed forms (j = 0 is averaged SGD; exact quadratic lands on A^-1 b),
  * invariants of eq. (3) (secant-inverse on span{u_k}, identity on its
  * complement), engineered spectra for the cutoff rule, a library eigensolver
- * for the Jacobi routine, and literal-vs-closed-form agreement.
+ * for the Jacobi routine, and literal-vs-closed-form agreement.  The capped
+ * step size has no formula in the paper: its two readings are pinned against
+ * library singular values and closed forms (H = h I, diagonal H).
  */
 #ifndef QN_ORACLE_H
 #define QN_ORACLE_H
@@ -107,6 +109,32 @@ int qno_coefficients(const double *C, const double *w, int m, double lambda,
 void qno_apply_closed_form(const void *thetas, const void *grads, int dtype,
                            int64_t rows, int m, int64_t ld, const double *c,
                            double tau, double *theta_new);
+
+/* ---- step size capped by 1 / sigma_max (Section 3, closing discussion) ----
+ * The paper caps tau at the reciprocal of the largest singular value that the
+ * method "approximates", without a formula.  Two readings are evaluated:
+ *   QNO_BOUND_SIGMA1: sigma_max := sigma_1, the largest entry of Sigma_G;
+ *   QNO_BOUND_SECANT: sigma_max := max_{k<=j} ||G v_k|| / ||Theta v_k||, the
+ *     largest gain of the approximated Hessian along its own secant
+ *     directions (eq. (3) maps u_k to y_k / sigma_k, so the forward map sends
+ *     y_k = Theta v_k to sigma_k u_k = G v_k).  j = 0 leaves tau unchanged; a
+ *     vanishing ||Theta v_k|| makes the estimate infinite and the cap zero.
+ * Both return min(tau, 1 / sigma_max) and store sigma_max if asked. */
+typedef enum { QNO_BOUND_SIGMA1 = 1, QNO_BOUND_SECANT = 2 } qno_bound;
+
+/* Literal: forms G v_k and Theta v_k as n-vectors and takes their 2-norms
+ * (Theta, G centred n x m doubles, ld = n; V from the eigendecomposition). */
+double qno_tau_bounded_literal(double tau, int mode, const double *Theta,
+                               const double *G, int64_t n, int m,
+                               const double *sigma, const double *V, int j,
+                               double *sigma_max);
+
+/* The same from m x m quantities, for large n: ||Theta v_k||^2 =
+ * v_k^T (Theta^T Theta) v_k with Ct = Theta^T Theta accumulated by
+ * qno_gram_accumulate over the theta columns; ||G v_k|| = sigma_k. */
+double qno_tau_bounded_from_gram(double tau, int mode, const double *Ct, int m,
+                                 const double *sigma, const double *V, int j,
+                                 double *sigma_max);
 
 #ifdef __cplusplus
 }

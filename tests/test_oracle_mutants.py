@@ -40,6 +40,17 @@ MUTANTS = [
     ("bf16 shift", "<< 16;", "<< 15;"),
     ("transposed eigenvector storage", "c[r] += Vl[k * m + r] * a / sg[k];",
      "c[r] += Vl[r * m + k] * a / sg[k];"),
+    ("cap from the eigenvalue", "return cap_tau(tau, s2 > 0.0, sqrt(s2), sigma_max);",
+     "return cap_tau(tau, s2 > 0.0, s2, sigma_max);"),
+    ("cap is a floor", "return fmin(tau, 1.0 / smax);", "return fmax(tau, 1.0 / smax);"),
+    ("secant quotient inverted", "const double q = sqrt(g2) / sqrt(y2);",
+     "const double q = sqrt(y2) / sqrt(g2);"),
+    ("secant norm from G", "yv += Theta[(int64_t)r * n + i] * V[k * m + r];",
+     "yv += G[(int64_t)r * n + i] * V[k * m + r];"),
+    ("secant from Gram without the root", "sigma[k] / sqrt(y2 > 0.0 ? y2 : 0.0);",
+     "sigma[k] / (y2 > 0.0 ? y2 : 0.0);"),
+    ("secant from Gram transposed V", "row += Ct[q * m + r] * V[k * m + q];",
+     "row += Ct[q * m + r] * V[q * m + k];"),
 ]
 
 

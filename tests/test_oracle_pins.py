@@ -407,3 +407,94 @@ def test_metamorphic_relations():
     r = oracle.update_literal(th, 2.0 * gr, tau, lam)
     assert r["j"] == base["j"]
     assert np.allclose(r["sigma"], 2.0 * base["sigma"], rtol=1e-12, atol=1e-14)
+
+
+# --------------------------------------------------------------------------
+# T9: step size capped by 1/sigma_max (Section 3, closing discussion).  The
+# paper gives no formula; both readings are pinned against what the
+# mathematics fixes.
+# --------------------------------------------------------------------------
+def _decomposed(th, gr, lam):
+    tb, gb = oracle.row_means(th), oracle.row_means(gr)
+    Theta, G = oracle.centre(th, tb), oracle.centre(gr, gb)
+    mu, V, _ = oracle.jacobi_eigh(oracle.gram(G))
+    sigma = oracle.sigma_from_mu(mu)
+    return Theta, G, sigma, V, oracle.select_j(sigma, lam)
+
+
+def test_cap_sigma1_is_the_library_spectral_norm_of_G():
+    rng = np.random.default_rng(41)
+    th, gr, _, _ = engineered(300, 6, [4.0, 2.0, 1.0, 0.5, 0.25], rng)
+    Theta, G, sigma, V, j = _decomposed(th, gr, 0.1)
+    s1 = np.linalg.svd(G, compute_uv=False)[0]
+    assert abs(s1 - 4.0) <= 1e-12
+    for fn_args in (lambda t: oracle.tau_bounded_literal(t, oracle.BOUND_SIGMA1, Theta, G, sigma, V, j),
+                    lambda t: oracle.tau_bounded_from_gram(t, oracle.BOUND_SIGMA1, oracle.gram(Theta), sigma, V, j)):
+        t, smax = fn_args(1.0)
+        assert abs(smax - s1) <= 1e-12 and abs(t - 0.25) <= 1e-13      # capped
+        t, smax = fn_args(0.1)
+        assert t == 0.1                                               # below the cap: untouched
+    # all gradients equal: no spectrum, no cap
+    same = np.tile(gr[:1].astype(np.float32), (6, 1))      # fp32 values: their mean is exact
+    Theta, G, sigma, V, j = _decomposed(th, same, 0.1)
+    assert oracle.tau_bounded_literal(3.0, oracle.BOUND_SIGMA1, Theta, G, sigma, V, j) == (3.0, 0.0)
+    assert oracle.tau_bounded_from_gram(3.0, oracle.BOUND_SIGMA1, oracle.gram(Theta), sigma, V, j) == (3.0, 0.0)
+
+
+def test_cap_secant_recovers_scalar_and_top_curvature():
+    rng = np.random.default_rng(43)
+    n, m = 120, 7
+    thetas = rng.standard_normal((m, n))
+    # H = h I: every secant quotient is h exactly
+    h = 3.5
+    grads = h * thetas - rng.standard_normal(n)[None, :]
+    Theta, G, sigma, V, j = _decomposed(thetas, grads, 0.01)
+    assert j == m - 1
+    for t, smax in (oracle.tau_bounded_literal(1.0, oracle.BOUND_SECANT, Theta, G, sigma, V, j),
+                    oracle.tau_bounded_from_gram(1.0, oracle.BOUND_SECANT, oracle.gram(Theta), sigma, V, j)):
+        assert abs(smax - h) <= 1e-11 and abs(t - 1.0 / h) <= 1e-12
+    # diagonal H, workers spread along coordinate axes only: G v_k = H Theta v_k
+    # lives on those axes, the largest quotient is the largest curvature among
+    # them when the stiffest axis is resolved on its own (far larger spread)
+    a = rng.uniform(0.1, 1.0, n)
+    a[5] = 40.0
+    thetas = np.zeros((m, n))
+    W = centred_basis(m, rng)                              # orthogonal worker patterns
+    thetas[:, 5] = W[:, 0]                                 # stiff axis
+    thetas[:, 17] = 1e-3 * W[:, 1]                         # one flat axis, tiny spread
+    grads = a[None, :] * thetas
+    Theta, G, sigma, V, j = _decomposed(thetas, grads, 1e-6)
+    assert j == 2
+    t, smax = oracle.tau_bounded_literal(1.0, oracle.BOUND_SECANT, Theta, G, sigma, V, j)
+    assert abs(smax - 40.0) <= 1e-9 and abs(t - 1.0 / smax) <= 1e-15
+    # j limits the directions looked at: only v_1 (the stiff one) here too
+    t1, smax1 = oracle.tau_bounded_literal(1.0, oracle.BOUND_SECANT, Theta, G, sigma, V, 1)
+    assert abs(smax1 - 40.0) <= 1e-9
+    # j = 0: nothing resolved, tau untouched
+    assert oracle.tau_bounded_literal(0.7, oracle.BOUND_SECANT, Theta, G, sigma, V, 0) == (0.7, 0.0)
+    assert oracle.tau_bounded_from_gram(0.7, oracle.BOUND_SECANT, oracle.gram(Theta), sigma, V, 0) == (0.7, 0.0)
+
+
+def test_cap_secant_is_a_quotient_of_H_and_both_forms_agree():
+    rng = np.random.default_rng(47)
+    n, m = 60, 9
+    A = random_spd(n, rng, 0.3, 6.0)
+    thetas = rng.standard_normal((m, n))
+    grads = quadratic_workers(A, rng.standard_normal(n), thetas)
+    Theta, G, sigma, V, j = _decomposed(thetas, grads, 0.05)
+    assert 0 < j <= m - 1
+    t, smax = oracle.tau_bounded_literal(10.0, oracle.BOUND_SECANT, Theta, G, sigma, V, j)
+    # each quotient is ||A y|| / ||y||: inside [sigma_min(A), sigma_max(A)]
+    assert 0.3 - 1e-9 <= smax <= 6.0 + 1e-9
+    # and equals the largest one formed by hand from the library's SVD of G
+    Uo, so, Vto = np.linalg.svd(G.T, full_matrices=False)      # G.T is n x m
+    quot = [so[k] / np.linalg.norm(Theta.T @ Vto[k]) for k in range(j)]
+    assert abs(smax - max(quot)) <= 1e-9 * smax
+    assert abs(t - 1.0 / max(quot)) <= 1e-9
+    t2, smax2 = oracle.tau_bounded_from_gram(10.0, oracle.BOUND_SECANT, oracle.gram(Theta), sigma, V, j)
+    assert abs(smax2 - smax) <= 1e-10 * smax and abs(t2 - t) <= 1e-12
+    # a direction with no parameter spread: infinite estimate, zero cap
+    thetas0 = np.tile(thetas[:1].astype(np.float32), (m, 1))
+    Theta0, G0, sigma0, V0, j0 = _decomposed(thetas0, grads, 0.05)
+    t0, s0 = oracle.tau_bounded_literal(1.0, oracle.BOUND_SECANT, Theta0, G0, sigma0, V0, j0)
+    assert t0 == 0.0 and np.isinf(s0)
