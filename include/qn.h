@@ -178,6 +178,33 @@ int qn_hinv_apply_ex(const void *thetas, const void *grads, int dtype, const flo
                      int64_t n, int m, int64_t ld, const float *c, float *out,
                      qn_stream_t stream);
 
+/* ---- step size capped by 1 / sigma_max (Section 3, closing discussion) ------
+ * The paper bounds tau above by the reciprocal of the largest singular value
+ * that the method approximates and gives no formula for it.  Two estimates:
+ *   QN_BOUND_SIGMA1 : sigma_1, the largest singular value of G;
+ *   QN_BOUND_SECANT : max_{k<=j} ||G v_k|| / ||Theta v_k||, the largest gain of
+ *                     the approximated Hessian along its secant directions
+ *                     (j = 0: no estimate, tau is left alone; a vanishing
+ *                     ||Theta v_k|| gives an infinite estimate and tau = 0).
+ * The comparison is made in double; tau_eff = min(tau, 1 / sigma_max).
+ *
+ * qn_update_bounded_ex : qn_update_ex with tau replaced by tau_eff.  tau_out
+ *   (device, 1 float, may be NULL) receives tau_eff.  QN_BOUND_SECANT adds one
+ *   Gram pass over thetas (n*m elements read) for Theta^T Theta.
+ * qn_tau_bound : the m x m piece alone.  sigma, V as written by qn_eig, j read
+ *   from device memory, C_theta = Theta^T Theta (m x m doubles, e.g. the C that
+ *   qn_gram_ex returns for the theta columns; unused and may be NULL for
+ *   QN_BOUND_SIGMA1).  tau_out: device float; sigma_max_out: device double,
+ *   may be NULL (0 when there is no estimate). */
+typedef enum { QN_BOUND_SIGMA1 = 1, QN_BOUND_SECANT = 2 } qn_bound;
+int qn_update_bounded_ex(const void *thetas, const void *grads, int dtype, int64_t n,
+                         int m, int64_t ld, float tau, float lambda, int mode,
+                         float *theta_new, int *j_out, float *tau_out,
+                         qn_stream_t stream);
+int qn_tau_bound(const double *sigma, const double *V, const int *j,
+                 const double *C_theta, int m, float tau, int mode, float *tau_out,
+                 double *sigma_max_out, qn_stream_t stream);
+
 /* ---- per-kernel timing (host side helper, for benchmarks) -----------------
  * Between qn_trace_begin() and qn_trace_end() every kernel the library
  * launches is bracketed by HIP events recorded on the launch stream.
@@ -194,7 +221,8 @@ enum {
     QN_K_APPLY = 4,    /* streaming pass over thetas and grads */
     QN_K_GEMV = 5,     /* G^T z: streaming pass over grads and z, and its reduce */
     QN_K_COEF = 6,     /* coefficients from sigma, V, j, w */
-    QN_TRACE_KERNELS = 7
+    QN_K_BOUND = 7,    /* capped step size from sigma, V, j (and Theta^T Theta) */
+    QN_TRACE_KERNELS = 8
 };
 int qn_trace_begin(int max_launches);
 int qn_trace_end(double *ms_sum /* host */, int *launches /* host */);

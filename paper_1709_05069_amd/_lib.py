@@ -36,6 +36,9 @@ SIGNATURES = {
     "qn_coef": (_int, [_vp, _vp, _vp, _vp, _int, _vp, _vp]),
     "qn_hinv_apply_ex": (_int, [_vp, _vp, _int, _vp, _i64, _int, _i64, _vp, _vp,
                                 _vp]),
+    "qn_update_bounded_ex": (_int, [_vp, _vp, _int, _i64, _int, _i64, _f32, _f32, _int,
+                                    _vp, _vp, _vp, _vp]),
+    "qn_tau_bound": (_int, [_vp, _vp, _vp, _vp, _int, _f32, _int, _vp, _vp, _vp]),
     "qn_probe_copy": (_int, [_vp, _vp, _i64, _vp]),
     "qn_probe_read": (_int, [_vp, _i64, _vp, _vp]),
     "qn_probe_sink_floats": (_int, []),

@@ -80,6 +80,11 @@ def run(n=100_000, m=16, iters=40, server="qn", tau=1.0, lam=0.1, eta=2e-3,
             js.append(int(j.item()))
             if on_step is not None:
                 on_step(it, thetas, grads, theta, js[-1])
+        elif server in ("qn_sigma1", "qn_secant"):
+            # the same step with tau capped at 1 / sigma_max (Section 3, closing discussion)
+            mode = qn.BOUND_SIGMA1 if server == "qn_sigma1" else qn.BOUND_SECANT
+            theta, j, _ = qn.qn_update_bounded(thetas, grads, tau, lam, mode)
+            js.append(int(j.item()))
         elif server == "sgd":
             theta = thetas.mean(0) - tau * grads.mean(0)
         else:

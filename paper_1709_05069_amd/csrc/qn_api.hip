@@ -41,7 +41,7 @@ int get_workspace(Workspace **out)
         const size_t b_w = align_up(sizeof(double) * QN_MAX_M, 256);
         const size_t b_c = align_up(sizeof(float) * QN_MAX_M, 256);
         const size_t b_gp = align_up(sizeof(double) * kGemvMaxBlocks * QN_MAX_M, 256);
-        ws.bytes = b_part + b_mraw + 2 * b_C + 3 * b_w + 2 * b_c + b_gp;
+        ws.bytes = b_part + b_mraw + 3 * b_C + 4 * b_w + 3 * b_c + b_gp;
         if (hipMalloc(&ws.base, ws.bytes) != hipSuccess) {
             (void)hipGetLastError();
             return QN_ENOMEM;
@@ -56,6 +56,9 @@ int get_workspace(Workspace **out)
         ws.sigma = reinterpret_cast<double *>(p); p += b_w;
         ws.wz = reinterpret_cast<double *>(p); p += b_w;
         ws.cz = reinterpret_cast<float *>(p); p += b_c;
+        ws.Ct = reinterpret_cast<double *>(p); p += b_C;
+        ws.wt = reinterpret_cast<double *>(p); p += b_w;
+        ws.tau_eff = reinterpret_cast<float *>(p); p += b_c;
         ws.gemv_partials = reinterpret_cast<double *>(p);
         g_ws[dev] = ws;
         g_ws_ready[dev] = true;
@@ -123,6 +126,7 @@ const char *qn_kernel_name(int kernel_id)
     case QN_K_APPLY: return "apply_kernel";
     case QN_K_GEMV: return "gemv_t";
     case QN_K_COEF: return "coef";
+    case QN_K_BOUND: return "tau_bound";
     default: return "unknown";
     }
 }
@@ -186,7 +190,7 @@ int qn_apply_ex(const void *thetas, const void *grads, int dtype, int64_t n,
     const int rc = get_workspace(&ws);
     if (rc != QN_OK)
         return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, c, nullptr, tau, theta_new,
+    return launch_apply(thetas, grads, dtype, n, m, ld, c, nullptr, tau, nullptr, theta_new,
                         ws->cu_count, static_cast<hipStream_t>(stream));
 }
 
@@ -208,7 +212,7 @@ int qn_update_ex(const void *thetas, const void *grads, int dtype, int64_t n,
     rc = launch_eig(ws->C, ws->w, m, lambda, nullptr, nullptr, ws->c, j_out, s);
     if (rc != QN_OK)
         return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, nullptr, tau, theta_new,
+    return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, nullptr, tau, nullptr, theta_new,
                         ws->cu_count, s);
 }
 

@@ -184,10 +184,12 @@ template <int DT, int MC, bool VEC>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
     const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
     int m_rt, int64_t ld, const float *__restrict__ c,
-    const float *__restrict__ z, float tau, float *__restrict__ out)
+    const float *__restrict__ z, float tau_host, const float *__restrict__ tau_dev,
+    float *__restrict__ out)
 {
     constexpr int R = VEC ? (DT == QN_F32 ? 4 : 8) : 1;
     const int m = MC ? MC : m_rt;
+    const float tau = tau_dev != nullptr ? *tau_dev : tau_host;   // uniform
     float csum = 0.0f;
     for (int k = 0; k < m; ++k)
         csum += c[k];
@@ -238,8 +240,10 @@ template <int DT, int MC>
 __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
     const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
     int m_rt, int64_t ld, const float *__restrict__ c,
-    const float *__restrict__ z, float tau, float *__restrict__ out, int steps)
+    const float *__restrict__ z, float tau_host, const float *__restrict__ tau_dev,
+    float *__restrict__ out, int steps)
 {
+    const float tau = tau_dev != nullptr ? *tau_dev : tau_host;   // uniform
     constexpr int kStagedThreads = StagedThreads<DT>::value;
     constexpr int R = DT == QN_F32 ? 4 : 8;        // rows per lane per step
     constexpr int Q = R / 4;                       // 128-bit results per lane per step
@@ -290,7 +294,7 @@ enum class ApplyShape { kElementwise, kDirect, kStaged };
 template <int DT, int MC>
 static void launch_mc(ApplyShape shape, int grid, const void *thetas, const void *grads,
                       int64_t n, int m, int64_t ld, const float *c, const float *z, float tau,
-                      float *out, hipStream_t stream)
+                      const float *tau_dev, float *out, hipStream_t stream)
 {
     if (shape == ApplyShape::kStaged) {
         // slab length: every block gets the same number of (nearly) full slabs
@@ -300,29 +304,29 @@ static void launch_mc(ApplyShape shape, int grid, const void *thetas, const void
         const int64_t rounds = (per_thread + staged_max_steps<DT>() - 1) / staged_max_steps<DT>();
         const int steps = static_cast<int>((per_thread + rounds - 1) / rounds);
         hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(grid), dim3(StagedThreads<DT>::value),
-                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, z, tau, out, steps);
+                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, steps);
         return;
     }
     if (shape == ApplyShape::kDirect)
         hipLaunchKernelGGL((apply_kernel<DT, MC, true>), dim3(grid), dim3(kApplyThreads),
-                           0, stream, thetas, grads, n, m, ld, c, z, tau, out);
+                           0, stream, thetas, grads, n, m, ld, c, z, tau, tau_dev, out);
     else
         hipLaunchKernelGGL((apply_kernel<DT, MC, false>), dim3(grid), dim3(kApplyThreads),
-                           0, stream, thetas, grads, n, m, ld, c, z, tau, out);
+                           0, stream, thetas, grads, n, m, ld, c, z, tau, tau_dev, out);
 }
 
 template <int DT>
 static void launch_dt(ApplyShape shape, int grid, const void *thetas, const void *grads,
                       int64_t n, int m, int64_t ld, const float *c, const float *z, float tau,
-                      float *out, hipStream_t stream)
+                      const float *tau_dev, float *out, hipStream_t stream)
 {
     switch (m) {
-    case 4: launch_mc<DT, 4>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    case 8: launch_mc<DT, 8>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    case 16: launch_mc<DT, 16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    case 32: launch_mc<DT, 32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    case 64: launch_mc<DT, 64>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
-    default: launch_mc<DT, 0>(shape, grid, thetas, grads, n, m, ld, c, z, tau, out, stream); break;
+    case 4: launch_mc<DT, 4>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
+    case 8: launch_mc<DT, 8>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
+    case 16: launch_mc<DT, 16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
+    case 32: launch_mc<DT, 32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
+    case 64: launch_mc<DT, 64>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
+    default: launch_mc<DT, 0>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
     }
 }
 
@@ -344,7 +348,7 @@ int setup_apply_kernels()
 
 int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
                  int m, int64_t ld, const float *c, const float *z, float tau,
-                 float *theta_new, int cu_count, hipStream_t stream)
+                 const float *tau_dev, float *theta_new, int cu_count, hipStream_t stream)
 {
     // 128-bit accesses work at element alignment (see v4f_elem), so the wide path
     // serves every input; the element-wise kernel remains as the shape for
@@ -366,9 +370,9 @@ int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
 
     TraceScope ts(QN_K_APPLY, stream);
     if (dtype == QN_F32)
-        launch_dt<QN_F32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, theta_new, stream);
+        launch_dt<QN_F32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, theta_new, stream);
     else
-        launch_dt<QN_BF16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, theta_new, stream);
+        launch_dt<QN_BF16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, theta_new, stream);
     return check_launch();
 }
 

@@ -278,7 +278,7 @@ int qn_hinv_apply_ex(const void *thetas, const void *grads, int dtype, const flo
     const int rc = get_workspace(&ws);
     if (rc != QN_OK)
         return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, c, z, 0.0f, out, ws->cu_count,
+    return launch_apply(thetas, grads, dtype, n, m, ld, c, z, 0.0f, nullptr, out, ws->cu_count,
                         static_cast<hipStream_t>(stream));
 }
 
@@ -306,7 +306,7 @@ int qn_hinv_ex(const void *thetas, const void *grads, int dtype, const float *z,
     rc = launch_coef(ws->sigma, ws->V, j_out, ws->wz, m, ws->cz, s);
     if (rc != QN_OK)
         return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, ws->cz, z, 0.0f, out,
+    return launch_apply(thetas, grads, dtype, n, m, ld, ws->cz, z, 0.0f, nullptr, out,
                         ws->cu_count, s);
 }
 

@@ -36,6 +36,9 @@ struct Workspace {
     double *V;          // QN_MAX_M * QN_MAX_M
     double *wz;         // QN_MAX_M
     float *cz;          // QN_MAX_M
+    double *Ct;         // QN_MAX_M * QN_MAX_M: Theta^T Theta for the secant bound
+    double *wt;         // QN_MAX_M: by-product of that Gram pass (unused)
+    float *tau_eff;     // 1: capped step size
     double *gemv_partials;   // kGemvMaxBlocks * QN_MAX_M
     void *base;
     size_t bytes;
@@ -57,16 +60,21 @@ int launch_eig(const double *C, const double *w, int m, float lambda,
                double *sigma, double *V, float *c, int *j_out,
                hipStream_t stream);
 // z == nullptr: theta_new = theta_bar - tau (g_bar + (Theta - G) c);
-// z != nullptr: theta_new = z + (Theta - G) c  (tau unused)
+// z != nullptr: theta_new = z + (Theta - G) c  (tau unused);
+// tau_dev != nullptr: tau is read from device memory instead of the argument
 int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
                  int m, int64_t ld, const float *c, const float *z, float tau,
-                 float *theta_new, int cu_count, hipStream_t stream);
+                 const float *tau_dev, float *theta_new, int cu_count, hipStream_t stream);
 // w = G^T z (m doubles) for the centred gradient matrix G
 int launch_gemv_t(const void *grads, int dtype, const float *z, int64_t n, int m,
                   int64_t ld, Workspace *ws, double *w, hipStream_t stream);
 // c = sum_{k < j} v_k (v_k^T w) / sigma_k^2, j read from device memory
 int launch_coef(const double *sigma, const double *V, const int *j, const double *w,
                 int m, float *c, hipStream_t stream);
+// tau_out = min(tau, 1 / sigma_max) for the estimate named by mode (a qn_bound)
+int launch_tau_bound(int mode, float tau, const double *sigma, const double *V,
+                     const int *j, const double *Ct, int m, float *tau_out,
+                     double *sigma_max_out, hipStream_t stream);
 
 // ---- tracing ------------------------------------------------------------------
 // RAII bracket: records a start/stop event pair around one kernel launch when

@@ -13,7 +13,7 @@ from . import _lib
 
 QN_F32, QN_BF16 = 0, 1
 KERNEL_NAMES = ("gram_stage1", "gram_reduce", "gram_project", "eig_select",
-                "apply_kernel", "gemv_t", "coef")
+                "apply_kernel", "gemv_t", "coef", "tau_bound")
 
 
 class QnError(RuntimeError):
@@ -184,6 +184,51 @@ def qn_hinv_apply(thetas, grads, z, c, out=None, stream=None):
                               m, ld, c.data_ptr(), out.data_ptr(), _stream(stream)),
            "qn_hinv_apply")
     return out
+
+
+BOUND_SIGMA1, BOUND_SECANT = 1, 2
+
+
+def qn_update_bounded(thetas, grads, tau, lam, mode, theta_new=None, j_out=None,
+                      tau_out=None, stream=None):
+    """The whole step with tau capped at 1 / sigma_max (mode: BOUND_SIGMA1 or
+    BOUND_SECANT).  Returns (theta_new, j_out, tau_out (1,) fp32 on device)."""
+    L = _lib.load()
+    dt, m, n, ld = _worker(thetas, "thetas")
+    if (dt, m, n, ld) != _worker(grads, "grads"):
+        raise QnError("thetas and grads must agree in dtype, shape and stride")
+    theta_new = _dev_out(theta_new, (n,), torch.float32, thetas.device, "theta_new")
+    j_out = _dev_out(j_out, (1,), torch.int32, thetas.device, "j_out")
+    tau_out = _dev_out(tau_out, (1,), torch.float32, thetas.device, "tau_out")
+    _check(L.qn_update_bounded_ex(thetas.data_ptr(), grads.data_ptr(), dt, n, m, ld,
+                                  float(tau), float(lam), int(mode),
+                                  theta_new.data_ptr(), j_out.data_ptr(),
+                                  tau_out.data_ptr(), _stream(stream)),
+           "qn_update_bounded")
+    return theta_new, j_out, tau_out
+
+
+def qn_tau_bound(sigma, V, j, C_theta, tau, mode, stream=None):
+    """(tau_eff (1,) fp32, sigma_max (1,) fp64) on device from qn_eig's sigma, V,
+    the device int j and C_theta = Theta^T Theta (None for BOUND_SIGMA1)."""
+    L = _lib.load()
+    m = sigma.shape[0]
+    ts = [sigma, V, j] + ([C_theta] if C_theta is not None else [])
+    ok = (sigma.dtype == torch.float64 and V.dtype == torch.float64 and
+          j.dtype == torch.int32 and tuple(V.shape) == (m, m) and j.numel() == 1 and
+          (C_theta is None or (C_theta.dtype == torch.float64 and
+                               tuple(C_theta.shape) == (m, m))) and
+          all(t.is_cuda and t.is_contiguous() for t in ts))
+    if not ok:
+        raise QnError("qn_tau_bound: sigma (m,), V (m, m), C_theta (m, m) float64 and "
+                      "j (1,) int32 on device")
+    tau_out = torch.empty(1, dtype=torch.float32, device=sigma.device)
+    smax = torch.empty(1, dtype=torch.float64, device=sigma.device)
+    _check(L.qn_tau_bound(sigma.data_ptr(), V.data_ptr(), j.data_ptr(),
+                          C_theta.data_ptr() if C_theta is not None else None, m,
+                          float(tau), int(mode), tau_out.data_ptr(), smax.data_ptr(),
+                          _stream(stream)), "qn_tau_bound")
+    return tau_out, smax
 
 
 def probe_copy(src, dst, stream=None):

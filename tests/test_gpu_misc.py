@@ -25,7 +25,7 @@ def test_trace_counts_every_kernel_once_per_update():
     tr = qn.trace_end()
     assert set(tr) == set(qn.KERNEL_NAMES)
     for name, (ms, cnt) in tr.items():
-        if name in ("gemv_t", "coef"):        # only the general-z operator runs these
+        if name in ("gemv_t", "coef", "tau_bound"):   # the general-z operator, the capped step
             assert cnt == 0
         else:
             assert cnt == 3 and ms > 0.0
