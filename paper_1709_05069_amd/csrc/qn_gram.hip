@@ -14,28 +14,31 @@
 // g_bar = s + (1/m) sum_k d_k, hence, at m x m size and in fp64,
 //     C = P N P,        w = P ( t + (1/m) N 1 ).
 //
-// Stage 1: one streaming pass over grads on v_mfma_f32_16x16x4_f32.  For a Gram
-//   product the A and B operands are the same register: lane l of a wavefront
-//   supplies column l%16 (and l%16 + 16 when m > 16) for the row slot l/16, and
-//   any assignment of rows to the four slots is valid as long as both operands
-//   agree.  The m columns form NT = 1..4 sets of 16 (m <= 16, 32, 48, 64) and
-//   only the lower triangle of the NT x NT tiling is computed (1, 3, 6 or 10
-//   tiles).  MFMA accumulators run in fp32 over one tile and are then added to
-//   per-lane fp64 totals; waves are combined through LDS in a fixed order and
-//   each block writes one partial.  No atomics.
-//   gram_stage1_stream: HBM -> LDS with coalesced direct-to-LDS loads carrying the
-//     non-temporal hint (128-bit per lane when the columns are 16-byte aligned:
-//     every wave instruction moves 1 KiB of one column; element-sized per lane
-//     otherwise), two LDS stages per block, two blocks per CU; the wavefronts
-//     then read their operands from LDS in the lane = column layout.
-//     Measured on MI355X this load pattern sustains about 7.0 TB/s, against
-//     6.4 TB/s when each lane fetches its own column straight from HBM.
-//     For bf16 storage the fp32 matrix cores would be the bottleneck (twice the
-//     elements per byte), so that path runs on v_mfma_f32_16x16x32_bf16: the
-//     shifted fp32 value is split into two bf16 terms and the four cross
-//     products are accumulated (exact for all but widely different magnitudes).
-//     (Unaligned bf16 input stays on the fp32 matrix cores: 2-byte direct-to-LDS
-//     loads land one value per dword.)
+// Stage 1: one streaming pass over grads on v_mfma_f32_16x16x32_bf16.  For a
+//   Gram product the A and B operands are the same register: lane l of a
+//   wavefront supplies column l%16 of a column set for the 8 rows of slot l/16,
+//   and any assignment of rows to the four slots is valid as long as both
+//   operands agree.  The m columns form NT = 1..4 sets of 16 (m <= 16, 32, 48, 64)
+//   and only the lower triangle of the NT x NT tiling is computed (1, 3, 6 or 10
+//   tiles).  The shifted fp32 entry is split into bf16 terms whose products the
+//   matrix cores form exactly and accumulate in fp32:
+//     fp32 storage: d = hi + mid + lo exactly (8 + 8 + 8 significant bits, by
+//       truncation); six products (all but mid lo, lo mid, lo lo, which are below
+//       2^-23 of the leading one).  This is both more accurate than fp32
+//       multiply-adds on v_mfma_f32_16x16x4_f32 and 2.7x cheaper in matrix-core
+//       cycles, which matters for m > 32 (ten tiles);
+//     bf16 storage: d = hi + lo (exact unless a value and the pivot differ by
+//       more than 2^8 in magnitude), four products.
+//   Accumulators run in fp32 over one tile and are then added to per-lane fp64
+//   totals; waves are combined through LDS in a fixed order and each block writes
+//   one partial.  No atomics.
+//   HBM -> LDS goes through coalesced direct-to-LDS loads carrying the
+//   non-temporal hint (128-bit per lane when the columns are 16-byte aligned:
+//   every wave instruction moves 1 KiB of one column; element-sized per lane
+//   otherwise, 2-byte loads landing one value per dword), two LDS stages per
+//   block; the wavefronts then read their operands from LDS in the lane = column
+//   layout.  Measured on MI355X this load pattern sustains about 7.0 TB/s,
+//   against 6.4 TB/s when each lane fetches its own column straight from HBM.
 // Stage 2 (gram_reduce): fixed-order fp64 sum of the block partials.
 // Stage 3 (gram_project): the m x m algebra above.
 #include "qn_internal.h"
@@ -95,10 +98,41 @@ __device__ __forceinline__ void lds_rows(const char *p, float (&x)[FMT == 1 ? 8 
     }
 }
 
-// d = present ? (keep_raw ? x : x - s) : 0 for 8 rows, split into bf16 hi + lo:
-// hi = the upper 16 bits of d, lo = bf16(d - hi).  Exact whenever d has at most
-// 16 significant bits (always, unless x and s differ by more than 2^8 in
-// magnitude), else good to 2^-16.
+// 8 consecutive rows of one column from LDS as fp32: one 16-byte vector of packed
+// bf16, or two vectors in the 4-bytes-per-row formats.
+template <int FMT>
+__device__ __forceinline__ void lds_rows8(const char *p, float (&x)[8])
+{
+    if constexpr (FMT == 1) {
+        lds_rows<1>(p, x);
+    } else {
+        float a[4], b[4];
+        lds_rows<FMT>(p, a);
+        lds_rows<FMT>(p + 16, b);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = a[e];
+            x[4 + e] = b[e];
+        }
+    }
+}
+
+// The shifted entry d = present ? (keep_raw ? x : x - s) : 0.
+__device__ __forceinline__ float shifted(float x, float s, bool present, bool keep_raw)
+{
+    return present ? (keep_raw ? x : x - s) : 0.0f;
+}
+
+// Upper halves of two fp32 words as a bf16 pair (truncation).
+__device__ __forceinline__ uint32_t upper_halves(uint32_t u0, uint32_t u1)
+{
+    return __builtin_amdgcn_perm(u1, u0, 0x07060302u);
+}
+
+// d for 8 rows, split into bf16 hi + lo: hi = the upper 16 bits of d,
+// lo = bf16(d - hi).  Exact whenever d has at most 16 significant bits (always
+// for bf16 storage, unless x and s differ by more than 2^8 in magnitude), else
+// good to 2^-16.
 __device__ __forceinline__ void split_bf16(const float (&x)[8], const float (&s)[8],
                                            bool present, bool keep_raw, v8bf &hi,
                                            v8bf &lo)
@@ -106,10 +140,10 @@ __device__ __forceinline__ void split_bf16(const float (&x)[8], const float (&s)
     uint32_t hw[4], lw[4];
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-        const float d0 = present ? (keep_raw ? x[2 * h] : x[2 * h] - s[2 * h]) : 0.0f;
-        const float d1 = present ? (keep_raw ? x[2 * h + 1] : x[2 * h + 1] - s[2 * h + 1]) : 0.0f;
+        const float d0 = shifted(x[2 * h], s[2 * h], present, keep_raw);
+        const float d1 = shifted(x[2 * h + 1], s[2 * h + 1], present, keep_raw);
         const uint32_t u0 = __float_as_uint(d0), u1 = __float_as_uint(d1);
-        hw[h] = __builtin_amdgcn_perm(u1, u0, 0x07060302u);      // upper halves of d0, d1
+        hw[h] = upper_halves(u0, u1);
         const float l0 = d0 - __uint_as_float(u0 & 0xffff0000u);
         const float l1 = d1 - __uint_as_float(u1 & 0xffff0000u);
         const v2bf lp = {static_cast<__bf16>(l0), static_cast<__bf16>(l1)};
@@ -117,6 +151,35 @@ __device__ __forceinline__ void split_bf16(const float (&x)[8], const float (&s)
     }
     const v4u hv = {hw[0], hw[1], hw[2], hw[3]}, lv = {lw[0], lw[1], lw[2], lw[3]};
     hi = __builtin_bit_cast(v8bf, hv);
+    lo = __builtin_bit_cast(v8bf, lv);
+}
+
+// d for 8 rows of fp32 storage, split exactly into three bf16 terms by
+// truncation: hi = the leading 8 significant bits of d, mid = the leading 8 of
+// d - hi, lo = the rest (at most 8 bits, so its upper half is all of it).
+__device__ __forceinline__ void split3_bf16(const float (&x)[8], const float (&s)[8],
+                                            bool present, bool keep_raw, v8bf &hi,
+                                            v8bf &mid, v8bf &lo)
+{
+    uint32_t hw[4], mw[4], lw[4];
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        const float d0 = shifted(x[2 * h], s[2 * h], present, keep_raw);
+        const float d1 = shifted(x[2 * h + 1], s[2 * h + 1], present, keep_raw);
+        const uint32_t u0 = __float_as_uint(d0), u1 = __float_as_uint(d1);
+        hw[h] = upper_halves(u0, u1);
+        const float r0 = d0 - __uint_as_float(u0 & 0xffff0000u);
+        const float r1 = d1 - __uint_as_float(u1 & 0xffff0000u);
+        const uint32_t v0 = __float_as_uint(r0), v1 = __float_as_uint(r1);
+        mw[h] = upper_halves(v0, v1);
+        const float l0 = r0 - __uint_as_float(v0 & 0xffff0000u);
+        const float l1 = r1 - __uint_as_float(v1 & 0xffff0000u);
+        lw[h] = upper_halves(__float_as_uint(l0), __float_as_uint(l1));
+    }
+    const v4u hv = {hw[0], hw[1], hw[2], hw[3]}, mv = {mw[0], mw[1], mw[2], mw[3]},
+              lv = {lw[0], lw[1], lw[2], lw[3]};
+    hi = __builtin_bit_cast(v8bf, hv);
+    mid = __builtin_bit_cast(v8bf, mv);
     lo = __builtin_bit_cast(v8bf, lv);
 }
 
@@ -137,7 +200,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     constexpr int FMT = DT == QN_F32 ? 0 : (WIDE ? 2 : 1);
     constexpr int RPV = 16 / LESZ;                       // rows per 16-byte LDS vector
     constexpr int SLOTS_PER_WAVE = 16 * NT / kGramWaves; // column slots a wave loads
-    constexpr int VEC_PER_GROUP = ROWS / kGramWaves / 4 / RPV;   // 2 in every format
+    constexpr int SLICES = ROWS / kGramWaves / 4 / 8;    // 8-row slices per lane group and tile
     constexpr int STAGE = stage_bytes<NT>();
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -233,46 +296,55 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
 #pragma unroll
         for (int t = 0; t < TILES; ++t)
             acc[t] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+        {
+            // The 8 rows a lane holds per column are one K-slice of
+            // v_mfma_f32_16x16x32_bf16.  The shifted fp32 value is split into bf16
+            // terms and the cross products that matter are accumulated in fp32.
 #pragma unroll
-        for (int i = 0; i < VEC_PER_GROUP; ++i) {
-            float x[NT][RPV], s[RPV];
-            lds_rows<FMT>(stage + byte0 + 16 * i, s);            // column 0: the pivot
+            for (int sl = 0; sl < SLICES; ++sl) {
+                const char *at = stage + byte0 + sl * 8 * LESZ;
+                float x[NT][8], s[8];
+                lds_rows8<FMT>(at, s);                           // column 0: the pivot
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
-                lds_rows<FMT>(stage + (col + 16 * t) * kColPitch + byte0 + 16 * i, x[t]);
-            if constexpr (FMT != 1) {
-                // fp32 matrix cores: one k-step of 4 rows per element of the vector
-#pragma unroll
-                for (int e = 0; e < RPV; ++e) {
-                    float d[NT];
+                for (int t = 0; t < NT; ++t)
+                    lds_rows8<FMT>(at + (col + 16 * t) * kColPitch, x[t]);
+                if constexpr (DT == QN_F32) {
+                    // d = hi + mid + lo exactly (8 + 8 + 8 bits); the six products
+                    // down to 2^-16 of the leading one are kept, the dropped ones
+                    // (mid lo, lo mid, lo lo) are below 2^-23 of it
+                    v8bf hi[NT], mid[NT], lo[NT];
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
-                        d[t] = has[t] ? ((t == 0 && is_pivot) ? x[t][e] : x[t][e] - s[e]) : 0.0f;
+                        split3_bf16(x[t], s, has[t], t == 0 && is_pivot, hi[t], mid[t], lo[t]);
 #pragma unroll
                     for (int ti = 0; ti < NT; ++ti)
 #pragma unroll
-                        for (int tj = 0; tj <= ti; ++tj)
-                            acc[tile_index(ti, tj)] = __builtin_amdgcn_mfma_f32_16x16x4f32(
-                                d[ti], d[tj], acc[tile_index(ti, tj)], 0, 0, 0);
+                        for (int tj = 0; tj <= ti; ++tj) {
+                            v4f &a = acc[tile_index(ti, tj)];
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], lo[tj], a, 0, 0, 0);
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo[ti], hi[tj], a, 0, 0, 0);
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mid[ti], mid[tj], a, 0, 0, 0);
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], mid[tj], a, 0, 0, 0);
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mid[ti], hi[tj], a, 0, 0, 0);
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], hi[tj], a, 0, 0, 0);
+                        }
+                } else {
+                    // bf16 storage: d = hi + lo, all four products
+                    v8bf hi[NT], lo[NT];
+#pragma unroll
+                    for (int t = 0; t < NT; ++t)
+                        split_bf16(x[t], s, has[t], t == 0 && is_pivot, hi[t], lo[t]);
+#pragma unroll
+                    for (int ti = 0; ti < NT; ++ti)
+#pragma unroll
+                        for (int tj = 0; tj <= ti; ++tj) {
+                            v4f &a = acc[tile_index(ti, tj)];
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo[ti], lo[tj], a, 0, 0, 0);
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], lo[tj], a, 0, 0, 0);
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo[ti], hi[tj], a, 0, 0, 0);
+                            a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], hi[tj], a, 0, 0, 0);
+                        }
                 }
-            } else {
-                // bf16 storage: the 8 rows a lane just read are one K-slice of
-                // v_mfma_f32_16x16x32_bf16; (hi + lo)(hi + lo)^T is expanded into
-                // its four products
-                v8bf hi[NT], lo[NT];
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    split_bf16(x[t], s, has[t], t == 0 && is_pivot, hi[t], lo[t]);
-#pragma unroll
-                for (int ti = 0; ti < NT; ++ti)
-#pragma unroll
-                    for (int tj = 0; tj <= ti; ++tj) {
-                        v4f &a = acc[tile_index(ti, tj)];
-                        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], hi[tj], a, 0, 0, 0);
-                        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi[ti], lo[tj], a, 0, 0, 0);
-                        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo[ti], hi[tj], a, 0, 0, 0);
-                        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo[ti], lo[tj], a, 0, 0, 0);
-                    }
             }
         }
 #pragma unroll
@@ -408,7 +480,9 @@ static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t 
 {
     const int rows = aligned ? StreamRows<DT, true>::value : StreamRows<DT, false>::value;
     const int64_t num_tiles = (n + rows - 1) / rows;
-    const int64_t cap = static_cast<int64_t>(cu_count) * stream_blocks_per_cu<NT>();
+    int64_t cap = static_cast<int64_t>(cu_count) * stream_blocks_per_cu<NT>();
+    if (cap > kGramMaxBlocks)       // the partials buffer holds this many blocks
+        cap = kGramMaxBlocks;
     const int grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
     if (aligned)
         hipLaunchKernelGGL((gram_stage1_stream<DT, NT, true>), dim3(grid), dim3(kGramThreads),
@@ -473,8 +547,6 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
                    ? launch_stage1_nt<QN_F32>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream)
                    : launch_stage1_nt<QN_BF16>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream);
     }
-    if (grid < 0 || grid > kGramMaxBlocks)
-        return QN_ELAUNCH;
     if (check_launch() != QN_OK) return QN_ELAUNCH;
     {
         TraceScope ts(QN_K_REDUCE, stream);
