@@ -40,7 +40,8 @@
  *   overlap in time (different streams or host threads) race and must be
  *   serialised by the caller.
  * Determinism: no floating-point atomics; the reduction tree is a function of
- *   (n, m, dtype) only, so results are bitwise reproducible run to run.
+ *   (n, m, dtype, alignment) and the device's compute-unit count only, so
+ *   results are bitwise reproducible run to run.
  * Errors: the return value is a qn_status.  Argument errors are detected on
  *   the host before anything is enqueued.  Data-dependent conditions are
  *   reported through j_out, never through the return value:
@@ -155,7 +156,9 @@ int qn_apply_ex(const void *thetas, const void *grads, int dtype, int64_t n,
  * the span.  Evaluated as z + (Theta - G) c_z with c_z = sum_{k<=j} v_k (v_k^T
  * G^T z) / sigma_k^2; qn_update is this operator applied to g_bar inside eq. (2).
  * z, out : n fp32 values (device); out must not overlap an input.
- * Three passes over memory (Gram, G^T z, apply); j_out as for qn_update. */
+ * Two passes over memory: the Gram pass carries z along and yields G^T z with
+ * G^T G; then the apply sweep.  j_out as for qn_update; a non-finite value in
+ * z is treated like one in grads (j_out = -1, out = z). */
 int qn_hinv(const float *thetas, const float *grads, const float *z, int64_t n, int m,
             float lambda, float *out, int *j_out, qn_stream_t stream);
 int qn_hinv_bf16(const uint16_t *thetas, const uint16_t *grads, const float *z,
@@ -165,7 +168,8 @@ int qn_hinv_ex(const void *thetas, const void *grads, int dtype, const float *z,
                int64_t n, int m, int64_t ld, float lambda, float *out, int *j_out,
                qn_stream_t stream);
 /* its pieces:
- * qn_gemv_t_ex     : w = G^T z (m doubles, device) for the centred G of grads;
+ * qn_gemv_t_ex     : w = G^T z (m doubles, device) for the centred G of grads
+ *                    (one Gram pass that carries z);
  * qn_coef          : c (m floats) = sum_{k<j} v_k (v_k^T w)/sigma_k^2 from sigma, V
  *                    as written by qn_eig and j read from device memory (*j <= 0
  *                    gives c = 0); re-centred like qn_eig's c;
@@ -219,10 +223,9 @@ enum {
     QN_K_PROJECT = 2,  /* m x m centring algebra producing C and w */
     QN_K_EIG = 3,      /* Jacobi + cutoff + coefficients */
     QN_K_APPLY = 4,    /* streaming pass over thetas and grads */
-    QN_K_GEMV = 5,     /* G^T z: streaming pass over grads and z, and its reduce */
-    QN_K_COEF = 6,     /* coefficients from sigma, V, j, w */
-    QN_K_BOUND = 7,    /* capped step size from sigma, V, j (and Theta^T Theta) */
-    QN_TRACE_KERNELS = 8
+    QN_K_COEF = 5,     /* coefficients from sigma, V, j, w */
+    QN_K_BOUND = 6,    /* capped step size from sigma, V, j (and Theta^T Theta) */
+    QN_TRACE_KERNELS = 7
 };
 int qn_trace_begin(int max_launches);
 int qn_trace_end(double *ms_sum /* host */, int *launches /* host */);

@@ -40,8 +40,7 @@ int get_workspace(Workspace **out)
         const size_t b_C = align_up(sizeof(double) * QN_MAX_M * QN_MAX_M, 256);
         const size_t b_w = align_up(sizeof(double) * QN_MAX_M, 256);
         const size_t b_c = align_up(sizeof(float) * QN_MAX_M, 256);
-        const size_t b_gp = align_up(sizeof(double) * kGemvMaxBlocks * QN_MAX_M, 256);
-        ws.bytes = b_part + b_mraw + 3 * b_C + 4 * b_w + 3 * b_c + b_gp;
+        ws.bytes = b_part + b_mraw + 3 * b_C + 4 * b_w + 3 * b_c;
         if (hipMalloc(&ws.base, ws.bytes) != hipSuccess) {
             (void)hipGetLastError();
             return QN_ENOMEM;
@@ -59,7 +58,6 @@ int get_workspace(Workspace **out)
         ws.Ct = reinterpret_cast<double *>(p); p += b_C;
         ws.wt = reinterpret_cast<double *>(p); p += b_w;
         ws.tau_eff = reinterpret_cast<float *>(p); p += b_c;
-        ws.gemv_partials = reinterpret_cast<double *>(p);
         g_ws[dev] = ws;
         g_ws_ready[dev] = true;
     }
@@ -124,7 +122,6 @@ const char *qn_kernel_name(int kernel_id)
     case QN_K_PROJECT: return "gram_project";
     case QN_K_EIG: return "eig_select";
     case QN_K_APPLY: return "apply_kernel";
-    case QN_K_GEMV: return "gemv_t";
     case QN_K_COEF: return "coef";
     case QN_K_BOUND: return "tau_bound";
     default: return "unknown";
@@ -163,7 +160,7 @@ int qn_gram_ex(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     const int rc = get_workspace(&ws);
     if (rc != QN_OK)
         return rc;
-    return launch_gram(grads, dtype, n, m, ld, ws, C, w, static_cast<hipStream_t>(stream));
+    return launch_gram(grads, dtype, n, m, ld, ws, nullptr, C, w, static_cast<hipStream_t>(stream));
 }
 
 int qn_eig(const double *C, const double *w, int m, float lambda, double *sigma,
@@ -206,7 +203,7 @@ int qn_update_ex(const void *thetas, const void *grads, int dtype, int64_t n,
     if (rc != QN_OK)
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = launch_gram(grads, dtype, n, m, ld, ws, ws->C, ws->w, s);
+    rc = launch_gram(grads, dtype, n, m, ld, ws, nullptr, ws->C, ws->w, s);
     if (rc != QN_OK)
         return rc;
     rc = launch_eig(ws->C, ws->w, m, lambda, nullptr, nullptr, ws->c, j_out, s);

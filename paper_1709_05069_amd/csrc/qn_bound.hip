@@ -106,7 +106,7 @@ int qn_update_bounded_ex(const void *thetas, const void *grads, int dtype, int64
     if (rc != QN_OK)
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = launch_gram(grads, dtype, n, m, ld, ws, ws->C, ws->w, s);
+    rc = launch_gram(grads, dtype, n, m, ld, ws, nullptr, ws->C, ws->w, s);
     if (rc != QN_OK)
         return rc;
     rc = launch_eig(ws->C, ws->w, m, lambda, ws->sigma, ws->V, ws->c, j_out, s);
@@ -114,7 +114,7 @@ int qn_update_bounded_ex(const void *thetas, const void *grads, int dtype, int64
         return rc;
     if (mode == QN_BOUND_SECANT) {
         // Theta^T Theta by the same centred Gram pass, over the theta columns
-        rc = launch_gram(thetas, dtype, n, m, ld, ws, ws->Ct, ws->wt, s);
+        rc = launch_gram(thetas, dtype, n, m, ld, ws, nullptr, ws->Ct, ws->wt, s);
         if (rc != QN_OK)
             return rc;
     }

@@ -63,8 +63,10 @@ __host__ __device__ constexpr int tile_index(int ti, int tj) { return ti * (ti +
 // LDS at slot * kColPitch (1 KiB + 16 B, which spreads the 16 columns a
 // quarter-wave reads over all banks).  16 * NT slots per stage, two stages.
 constexpr int kColPitch = 1040;                       // bytes per column slot
-template <int NT> constexpr int stage_bytes() { return 16 * NT * kColPitch; }
-template <int NT> constexpr int stream_lds_bytes() { return 2 * stage_bytes<NT>(); }
+// A pass that also carries a vector z (below) keeps z's rows of the tile in
+// ZSLOTS further slots of each stage (fp32: 1 KiB per 256 rows).
+template <int NT, int ZSLOTS> constexpr int stage_bytes() { return (16 * NT + ZSLOTS) * kColPitch; }
+template <int NT, int ZSLOTS> constexpr int stream_lds_bytes() { return 2 * stage_bytes<NT, ZSLOTS>(); }
 // blocks per CU that fit the 160 KiB of LDS (and 32 waves): 4, 2, 1, 1
 template <int NT> constexpr int stream_blocks_per_cu() { return NT == 1 ? 4 : (NT == 2 ? 2 : 1); }
 
@@ -187,10 +189,13 @@ __device__ __forceinline__ void split3_bf16(const float (&x)[8], const float (&s
 // a column's whole tile (1 KiB) per wave instruction.  Otherwise the same tile is
 // brought in with element-sized direct-to-LDS loads (64 consecutive rows per
 // wave instruction): still coalesced, any alignment, more instructions.
-template <int DT, int NT, bool ALIGNED>
+// HAS_Z: the pivot lane supplies z (n fp32 values) instead of the raw pivot
+// column, so the pass yields Q[k][0] = d_k^T z: the inner products G^T z are
+// built from (eq. (4)'s alpha_k for an arbitrary z) at no extra pass over grads.
+template <int DT, int NT, bool ALIGNED, bool HAS_Z>
 __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     const void *__restrict__ grads, int64_t n, int m, int64_t ld,
-    double *__restrict__ partials)
+    double *__restrict__ partials, const float *__restrict__ z, int z_aligned)
 {
     constexpr int TILES = GramTiles<NT>::value;
     constexpr int ROWS = StreamRows<DT, ALIGNED>::value; // rows per tile
@@ -201,7 +206,9 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     constexpr int RPV = 16 / LESZ;                       // rows per 16-byte LDS vector
     constexpr int SLOTS_PER_WAVE = 16 * NT / kGramWaves; // column slots a wave loads
     constexpr int SLICES = ROWS / kGramWaves / 4 / 8;    // 8-row slices per lane group and tile
-    constexpr int STAGE = stage_bytes<NT>();
+    constexpr int ZSLOTS = HAS_Z ? ROWS / 256 : 0;       // 1 KiB slots holding z's rows
+    constexpr int STAGE = stage_bytes<NT, ZSLOTS>();
+    constexpr int ZBASE = 16 * NT * kColPitch;           // z's rows inside a stage (contiguous)
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
     const int lane = threadIdx.x & 63;
@@ -269,6 +276,32 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
                 }
             }
         }
+        if constexpr (HAS_Z) {
+            // the last wave also brings in z's rows of the tile (fp32, contiguous)
+            if (wave == kGramWaves - 1) {
+                char *zl = stage + ZBASE;
+                if (row0 + ROWS <= n) {
+                    if (z_aligned) {
+#pragma unroll
+                        for (int part = 0; part < ROWS / 256; ++part)
+                            __builtin_amdgcn_global_load_lds(
+                                QN_GPTR(z + row0 + part * 256 + lane * 4),
+                                QN_LPTR(zl + part * 1024), 16, 0, 2);
+                    } else {
+#pragma unroll
+                        for (int part = 0; part < ROWS / 64; ++part)
+                            __builtin_amdgcn_global_load_lds(
+                                QN_GPTR(z + row0 + part * 64 + lane),
+                                QN_LPTR(zl + part * 256), 4, 0, 2);
+                    }
+                } else {
+                    for (int part = 0; part < ROWS / 64; ++part) {
+                        const int64_t r = row0 + part * 64 + lane;
+                        reinterpret_cast<float *>(zl)[part * 64 + lane] = r < n ? z[r] : 0.0f;
+                    }
+                }
+            }
+        }
     };
 
     double tot[TILES][4];
@@ -308,6 +341,17 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
                     lds_rows8<FMT>(at + (col + 16 * t) * kColPitch, x[t]);
+                [[maybe_unused]] v8bf zlo = {};                  // z's third term (bf16 storage)
+                if constexpr (HAS_Z) {
+                    // the same 8 rows of z; only the pivot lane uses them
+                    float zr[8];
+                    lds_rows8<0>(stage + ZBASE + (byte0 / LESZ + sl * 8) * 4, zr);
+                    if (is_pivot) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            x[0][e] = zr[e];
+                    }
+                }
                 if constexpr (DT == QN_F32) {
                     // d = hi + mid + lo exactly (8 + 8 + 8 bits); the six products
                     // down to 2^-16 of the leading one are kept, the dropped ones
@@ -334,6 +378,22 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
                         split_bf16(x[t], s, has[t], t == 0 && is_pivot, hi[t], lo[t]);
+                    if constexpr (HAS_Z) {
+                        // z is an arbitrary fp32 vector: its lane gets the exact
+                        // three-term split, the third term through one more product
+                        // per tile of column set 0
+                        v8bf zh, zm, zl3;
+                        split3_bf16(x[0], s, true, true, zh, zm, zl3);
+                        if (is_pivot) {
+                            hi[0] = zh;
+                            lo[0] = zm;
+                            zlo = zl3;
+                        }
+#pragma unroll
+                        for (int ti = 0; ti < NT; ++ti)
+                            acc[tile_index(ti, 0)] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                hi[ti], zlo, acc[tile_index(ti, 0)], 0, 0, 0);
+                    }
 #pragma unroll
                     for (int ti = 0; ti < NT; ++ti)
 #pragma unroll
@@ -430,10 +490,11 @@ __device__ __forceinline__ int raw_index(int k, int l)
     return (tile * 4 + (i & 3)) * 64 + (i >> 2) * 16 + j;
 }
 
-// C = P N P and w = P (t + N 1 / m) in fp64; one block.
+// C = P N P and w = P (t + N 1 / m) in fp64; one block.  z_mode: column 0 of the
+// raw matrix holds d_k^T z instead of d_k^T s, and w = G^T z = P t.
 constexpr int kProjectThreads = 1024;
 __global__ __launch_bounds__(kProjectThreads) void gram_project(
-    const double *__restrict__ mraw, int m, double *__restrict__ C,
+    const double *__restrict__ mraw, int m, int z_mode, double *__restrict__ C,
     double *__restrict__ w)
 {
     __shared__ double N[QN_MAX_M][QN_MAX_M + 1];
@@ -453,7 +514,7 @@ __global__ __launch_bounds__(kProjectThreads) void gram_project(
             s += N[threadIdx.x][x];
         rowsum[threadIdx.x] = s;
         const double t = threadIdx.x >= 1 ? mraw[raw_index(threadIdx.x, 0)] : 0.0;
-        u[threadIdx.x] = t + s / m;
+        u[threadIdx.x] = z_mode ? t : t + s / m;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -474,9 +535,10 @@ __global__ __launch_bounds__(kProjectThreads) void gram_project(
         w[threadIdx.x] = u[threadIdx.x] - umean;
 }
 
-template <int DT, int NT>
+template <int DT, int NT, bool HAS_Z>
 static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t n,
-                         int m, int64_t ld, double *partials, hipStream_t stream)
+                         int m, int64_t ld, double *partials, const float *z,
+                         hipStream_t stream)
 {
     const int rows = aligned ? StreamRows<DT, true>::value : StreamRows<DT, false>::value;
     const int64_t num_tiles = (n + rows - 1) / rows;
@@ -484,53 +546,68 @@ static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t 
     if (cap > kGramMaxBlocks)       // the partials buffer holds this many blocks
         cap = kGramMaxBlocks;
     const int grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
-    if (aligned)
-        hipLaunchKernelGGL((gram_stage1_stream<DT, NT, true>), dim3(grid), dim3(kGramThreads),
-                           stream_lds_bytes<NT>(), stream, grads, n, m, ld, partials);
-    else
-        hipLaunchKernelGGL((gram_stage1_stream<DT, NT, false>), dim3(grid), dim3(kGramThreads),
-                           stream_lds_bytes<NT>(), stream, grads, n, m, ld, partials);
+    const int z_aligned = reinterpret_cast<uintptr_t>(z) % 16 == 0;
+    if (aligned) {
+        constexpr int ZS = HAS_Z ? StreamRows<DT, true>::value / 256 : 0;
+        hipLaunchKernelGGL((gram_stage1_stream<DT, NT, true, HAS_Z>), dim3(grid),
+                           dim3(kGramThreads), (stream_lds_bytes<NT, ZS>()), stream, grads, n,
+                           m, ld, partials, z, z_aligned);
+    } else {
+        constexpr int ZS = HAS_Z ? StreamRows<DT, false>::value / 256 : 0;
+        hipLaunchKernelGGL((gram_stage1_stream<DT, NT, false, HAS_Z>), dim3(grid),
+                           dim3(kGramThreads), (stream_lds_bytes<NT, ZS>()), stream, grads, n,
+                           m, ld, partials, z, z_aligned);
+    }
     return grid;
 }
 
-template <int DT>
+template <int DT, bool HAS_Z>
 static int launch_stage1_nt(int nt, bool aligned, int cu_count, const void *grads,
                             int64_t n, int m, int64_t ld, double *partials,
-                            hipStream_t stream)
+                            const float *z, hipStream_t stream)
 {
     if (nt == 1)
-        return launch_stage1<DT, 1>(aligned, cu_count, grads, n, m, ld, partials, stream);
+        return launch_stage1<DT, 1, HAS_Z>(aligned, cu_count, grads, n, m, ld, partials, z, stream);
     if (nt == 2)
-        return launch_stage1<DT, 2>(aligned, cu_count, grads, n, m, ld, partials, stream);
+        return launch_stage1<DT, 2, HAS_Z>(aligned, cu_count, grads, n, m, ld, partials, z, stream);
     if (nt == 3)
-        return launch_stage1<DT, 3>(aligned, cu_count, grads, n, m, ld, partials, stream);
-    return launch_stage1<DT, 4>(aligned, cu_count, grads, n, m, ld, partials, stream);
+        return launch_stage1<DT, 3, HAS_Z>(aligned, cu_count, grads, n, m, ld, partials, z, stream);
+    return launch_stage1<DT, 4, HAS_Z>(aligned, cu_count, grads, n, m, ld, partials, z, stream);
 }
 
-// The streaming kernels use up to 130 KiB of dynamic LDS; the opt-in above the
+// The streaming kernels use up to 134 KiB of dynamic LDS; the opt-in above the
 // default 64 KiB is per device and is made once when the device's workspace is
 // set up.
+template <int DT, int NT, bool AL, bool HAS_Z>
+static bool opt_in_one()
+{
+    constexpr int ZS = HAS_Z ? StreamRows<DT, AL>::value / 256 : 0;
+    return hipFuncSetAttribute(
+               reinterpret_cast<const void *>(gram_stage1_stream<DT, NT, AL, HAS_Z>),
+               hipFuncAttributeMaxDynamicSharedMemorySize,
+               stream_lds_bytes<NT, ZS>()) == hipSuccess;
+}
+
+template <int DT, int NT>
+static bool opt_in_nt()
+{
+    return opt_in_one<DT, NT, true, false>() && opt_in_one<DT, NT, false, false>() &&
+           opt_in_one<DT, NT, true, true>() && opt_in_one<DT, NT, false, true>();
+}
+
+template <int DT>
+static bool opt_in_dt()
+{
+    return opt_in_nt<DT, 1>() && opt_in_nt<DT, 2>() && opt_in_nt<DT, 3>() && opt_in_nt<DT, 4>();
+}
+
 int setup_gram_kernels()
 {
-    bool ok = true;
-#define QN_OPT_IN(DTV, NTV, AL)                                                            \
-    ok = ok && hipFuncSetAttribute(                                                        \
-                   reinterpret_cast<const void *>(gram_stage1_stream<DTV, NTV, AL>),       \
-                   hipFuncAttributeMaxDynamicSharedMemorySize,                             \
-                   stream_lds_bytes<NTV>()) == hipSuccess
-#define QN_OPT_IN_ALL(DTV)                                                                 \
-    QN_OPT_IN(DTV, 1, true); QN_OPT_IN(DTV, 1, false); QN_OPT_IN(DTV, 2, true);            \
-    QN_OPT_IN(DTV, 2, false); QN_OPT_IN(DTV, 3, true); QN_OPT_IN(DTV, 3, false);          \
-    QN_OPT_IN(DTV, 4, true); QN_OPT_IN(DTV, 4, false)
-    QN_OPT_IN_ALL(QN_F32);
-    QN_OPT_IN_ALL(QN_BF16);
-#undef QN_OPT_IN_ALL
-#undef QN_OPT_IN
-    return ok ? QN_OK : QN_ELAUNCH;
+    return opt_in_dt<QN_F32>() && opt_in_dt<QN_BF16>() ? QN_OK : QN_ELAUNCH;
 }
 
 int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
-                Workspace *ws, double *C, double *w, hipStream_t stream)
+                Workspace *ws, const float *z, double *C, double *w, hipStream_t stream)
 {
     const size_t esz = dtype == QN_F32 ? 4 : 2;
     const bool aligned = (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
@@ -543,9 +620,14 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     int grid;
     {
         TraceScope ts(QN_K_GRAM, stream);
-        grid = dtype == QN_F32
-                   ? launch_stage1_nt<QN_F32>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream)
-                   : launch_stage1_nt<QN_BF16>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, stream);
+        if (z == nullptr)
+            grid = dtype == QN_F32
+                       ? launch_stage1_nt<QN_F32, false>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, z, stream)
+                       : launch_stage1_nt<QN_BF16, false>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, z, stream);
+        else
+            grid = dtype == QN_F32
+                       ? launch_stage1_nt<QN_F32, true>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, z, stream)
+                       : launch_stage1_nt<QN_BF16, true>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, z, stream);
     }
     if (check_launch() != QN_OK) return QN_ELAUNCH;
     {
@@ -557,7 +639,7 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     {
         TraceScope ts(QN_K_PROJECT, stream);
         hipLaunchKernelGGL(gram_project, dim3(1), dim3(kProjectThreads), 0, stream,
-                           ws->mraw, m, C, w);
+                           ws->mraw, m, z != nullptr ? 1 : 0, C, w);
     }
     return check_launch();
 }

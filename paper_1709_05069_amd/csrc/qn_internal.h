@@ -23,7 +23,6 @@ constexpr int kGramMaxBlocks = 1024;
 constexpr int kTileEntries = 256;               // 16 x 16
 constexpr int kMaxTiles = 10;                   // lower triangle of a 4x4 tiling (m <= 64)
 constexpr int kMaxEntries = kTileEntries * kMaxTiles;
-constexpr int kGemvMaxBlocks = 2048;
 
 // ---- per-device workspace ---------------------------------------------------
 struct Workspace {
@@ -39,7 +38,6 @@ struct Workspace {
     double *Ct;         // QN_MAX_M * QN_MAX_M: Theta^T Theta for the secant bound
     double *wt;         // QN_MAX_M: by-product of that Gram pass (unused)
     float *tau_eff;     // 1: capped step size
-    double *gemv_partials;   // kGemvMaxBlocks * QN_MAX_M
     void *base;
     size_t bytes;
     int cu_count;
@@ -54,8 +52,9 @@ int setup_apply_kernels();
 int setup_eig_kernels();
 
 // ---- kernel launchers (each enqueues on `stream`, returns a qn_status) ------
+// C = G^T G and, with z == nullptr, w = G^T g_bar; with z (n fp32 values) w = G^T z
 int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
-                Workspace *ws, double *C, double *w, hipStream_t stream);
+                Workspace *ws, const float *z, double *C, double *w, hipStream_t stream);
 int launch_eig(const double *C, const double *w, int m, float lambda,
                double *sigma, double *V, float *c, int *j_out,
                hipStream_t stream);
@@ -65,9 +64,6 @@ int launch_eig(const double *C, const double *w, int m, float lambda,
 int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
                  int m, int64_t ld, const float *c, const float *z, float tau,
                  const float *tau_dev, float *theta_new, int cu_count, hipStream_t stream);
-// w = G^T z (m doubles) for the centred gradient matrix G
-int launch_gemv_t(const void *grads, int dtype, const float *z, int64_t n, int m,
-                  int64_t ld, Workspace *ws, double *w, hipStream_t stream);
 // c = sum_{k < j} v_k (v_k^T w) / sigma_k^2, j read from device memory
 int launch_coef(const double *sigma, const double *V, const int *j, const double *w,
                 int m, float *c, hipStream_t stream);

@@ -13,7 +13,7 @@ from . import _lib
 
 QN_F32, QN_BF16 = 0, 1
 KERNEL_NAMES = ("gram_stage1", "gram_reduce", "gram_project", "eig_select",
-                "apply_kernel", "gemv_t", "coef", "tau_bound")
+                "apply_kernel", "coef", "tau_bound")
 
 
 class QnError(RuntimeError):

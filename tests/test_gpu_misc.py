@@ -25,7 +25,7 @@ def test_trace_counts_every_kernel_once_per_update():
     tr = qn.trace_end()
     assert set(tr) == set(qn.KERNEL_NAMES)
     for name, (ms, cnt) in tr.items():
-        if name in ("gemv_t", "coef", "tau_bound"):   # the general-z operator, the capped step
+        if name in ("coef", "tau_bound"):   # the general-z operator, the capped step
             assert cnt == 0
         else:
             assert cnt == 3 and ms > 0.0
@@ -36,12 +36,13 @@ def test_trace_counts_every_kernel_once_per_update():
     qn.qn_update(th, gr, wl.tau, wl.lam)
     tr = qn.trace_end()
     assert sum(c for _, c in tr.values()) == 2
-    # the operator on an arbitrary vector: 3 Gram kernels, eig, G^T z (+ its
-    # reduce), coefficients, apply
+    # the operator on an arbitrary vector: the Gram pass carries z, then the
+    # eigen kernel and the apply sweep
     qn.trace_begin(64)
     qn.qn_hinv(th, gr, torch.randn(th.shape[1], device=DEV), wl.lam)
     tr = qn.trace_end()
-    assert tr["gemv_t"][1] == 2 and tr["coef"][1] == 1 and tr["apply_kernel"][1] == 1
+    assert tr["gram_stage1"][1] == 1 and tr["eig_select"][1] == 1 and tr["apply_kernel"][1] == 1
+    assert tr["coef"][1] == 0
 
 
 def test_side_stream_gives_the_same_bits():

@@ -61,6 +61,7 @@ GRAM_CASES = [
     # more than 32 workers: the 4x4 tiling
     ("gpt2_small", 60000, 64), ("gpt2_small", 30001, 33), ("resnet50", 20480, 48),
     ("stress_1b_bf16", 40000, 64), ("stress_1b_bf16", 20003, 47),
+    ("gpt2_small", 20001, 64), ("stress_1b_bf16", 10001, 64),      # unaligned columns, four sets
 ]
 
 
