@@ -136,3 +136,28 @@ def test_hinv_j0_and_nonfinite():
     keep = torch.ones(10_000, dtype=torch.bool, device=DEV)
     keep[5] = False
     assert torch.equal(out[keep], z[keep])
+
+
+@pytest.mark.parametrize("name,n,m", [("gpt2_small", 33_000, 32), ("gpt2_small", 9_001, 64),
+                                      ("stress_1b_bf16", 20_480, 32), ("stress_1b_bf16", 7_777, 12),
+                                      ("small_mlp", 300, 8)])
+def test_z_at_any_alignment_gives_the_same_bits(name, n, m):
+    # z rides through the Gram pass in its own LDS slot, fetched with 16-byte or
+    # 4-byte direct-to-LDS loads depending on its address: same values, same bits
+    wl = replace(synth.WORKLOADS[name].scaled(n), m=m)
+    th, gr = synth.make_worker_states(wl, DEV)
+    g = torch.Generator(device=DEV)
+    g.manual_seed(n)
+    buf = torch.randn(n + 3, device=DEV, generator=g)
+    z0 = buf[:n].clone()
+    w0 = qn.qn_gemv_t(gr, z0)
+    out0, j0 = qn.qn_hinv(th, gr, z0, wl.lam)
+    for off in (1, 2, 3):
+        zo = torch.empty(n + 3, device=DEV)[off:off + n]
+        zo.copy_(z0)
+        assert zo.data_ptr() % 16 != 0
+        assert torch.equal(qn.qn_gemv_t(gr, zo), w0)
+        out, j = qn.qn_hinv(th, gr, zo, wl.lam)
+        assert int(j.item()) == int(j0.item()) and torch.equal(out, out0)
+    G = oracle.centre(synth.to_numpy_stored(gr), oracle.row_means(synth.to_numpy_stored(gr)))
+    assert rel(w0.cpu().numpy(), oracle.gemv_t(G, z0.cpu().numpy().astype(np.float64))) <= 1e-5
