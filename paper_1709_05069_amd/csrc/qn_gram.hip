@@ -20,7 +20,8 @@
 //   and any assignment of rows to the four slots is valid as long as both
 //   operands agree.  The m columns form NT = 1..4 sets of 16 (m <= 16, 32, 48, 64)
 //   and only the lower triangle of the NT x NT tiling is computed (1, 3, 6 or 10
-//   tiles).  The shifted fp32 entry is split into bf16 terms whose products the
+//   tiles).  For m <= 8 (<= 4) two (four) row blocks of the same columns share
+//   the 16 column lanes of the single set.  The shifted fp32 entry is split into bf16 terms whose products the
 //   matrix cores form exactly and accumulate in fp32:
 //     fp32 storage: d = hi + mid + lo exactly (8 + 8 + 8 significant bits, by
 //       truncation); six products (all but mid lo, lo mid, lo lo, which are below
@@ -67,8 +68,6 @@ constexpr int kColPitch = 1040;                       // bytes per column slot
 // ZSLOTS further slots of each stage (fp32: 1 KiB per 256 rows).
 template <int NT, int ZSLOTS> constexpr int stage_bytes() { return (16 * NT + ZSLOTS) * kColPitch; }
 template <int NT, int ZSLOTS> constexpr int stream_lds_bytes() { return 2 * stage_bytes<NT, ZSLOTS>(); }
-// blocks per CU that fit the 160 KiB of LDS (and 32 waves): 4, 2, 1, 1
-template <int NT> constexpr int stream_blocks_per_cu() { return NT == 1 ? 4 : (NT == 2 ? 2 : 1); }
 
 // Rows per tile.  bf16 inputs that are not 16-byte aligned arrive through
 // 2-byte direct-to-LDS loads, which the hardware stores zero-extended, one per
@@ -192,13 +191,20 @@ __device__ __forceinline__ void split3_bf16(const float (&x)[8], const float (&s
 // HAS_Z: the pivot lane supplies z (n fp32 values) instead of the raw pivot
 // column, so the pass yields Q[k][0] = d_k^T z: the inner products G^T z are
 // built from (eq. (4)'s alpha_k for an arbitrary z) at no extra pass over grads.
-template <int DT, int NT, bool ALIGNED, bool HAS_Z>
+// PACK (NT = 1 only): for m <= 8 (<= 4) the 16 column lanes hold PACK = 2 (4)
+// row blocks of the same 8 (4) columns side by side, so a tile covers PACK times
+// the rows; the output tile's PACK diagonal blocks are partial Gram matrices of
+// the same columns (summed in gram_project), its off-diagonal blocks are unused.
+template <int DT, int NT, bool ALIGNED, bool HAS_Z, int PACK>
 __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     const void *__restrict__ grads, int64_t n, int m, int64_t ld,
     double *__restrict__ partials, const float *__restrict__ z, int z_aligned)
 {
+    static_assert(PACK == 1 || NT == 1, "row blocks are packed only into a single column set");
     constexpr int TILES = GramTiles<NT>::value;
-    constexpr int ROWS = StreamRows<DT, ALIGNED>::value; // rows per tile
+    constexpr int ROWS = StreamRows<DT, ALIGNED>::value; // rows per column slot
+    constexpr int TROWS = ROWS * PACK;                   // rows per tile
+    constexpr int MP = 16 / PACK;                        // column lanes per row block
     constexpr int ESZ = (DT == QN_F32) ? 4 : 2;          // element size in memory
     constexpr bool WIDE = DT == QN_BF16 && !ALIGNED;     // bf16 kept one per dword in LDS
     constexpr int LESZ = WIDE ? 4 : ESZ;                 // element size in LDS
@@ -206,7 +212,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     constexpr int RPV = 16 / LESZ;                       // rows per 16-byte LDS vector
     constexpr int SLOTS_PER_WAVE = 16 * NT / kGramWaves; // column slots a wave loads
     constexpr int SLICES = ROWS / kGramWaves / 4 / 8;    // 8-row slices per lane group and tile
-    constexpr int ZSLOTS = HAS_Z ? ROWS / 256 : 0;       // 1 KiB slots holding z's rows
+    constexpr int ZSLOTS = HAS_Z ? TROWS / 256 : 0;      // 1 KiB slots holding z's rows
     constexpr int STAGE = stage_bytes<NT, ZSLOTS>();
     constexpr int ZBASE = 16 * NT * kColPitch;           // z's rows inside a stage (contiguous)
     extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -215,36 +221,40 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     const int wave = threadIdx.x >> 6;
     const int col = lane & 15;
     const int group = lane >> 4;
-    const bool is_pivot = col == 0;
+    const int sub = col / MP;                            // this lane's row block (0 when PACK = 1)
+    const bool is_pivot = col % MP == 0;
     bool has[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
-        has[t] = col + 16 * t < m;
+        has[t] = col % MP + 16 * t < m;
     const char *base = static_cast<const char *>(grads);
 
-    const int64_t num_tiles = (n + ROWS - 1) / ROWS;
+    const int64_t num_tiles = (n + TROWS - 1) / TROWS;
     const int64_t mine = (num_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
 
     // Brings tile number k of this block into LDS stage k % 2.
     auto fetch = [&](int64_t k) {
         const int64_t tile = blockIdx.x + k * gridDim.x;
-        const int64_t row0 = tile * ROWS;
+        const int64_t row0 = tile * TROWS;
         char *stage = lds + (k & 1) * STAGE;
-        if (row0 + ROWS <= n) {
+        // slot `slot` holds column slot % MP, rows [row0 + (slot / MP) * ROWS, + ROWS)
+        if (row0 + TROWS <= n) {
 #pragma unroll
             for (int jc = 0; jc < SLOTS_PER_WAVE; ++jc) {
-                const int c = wave * SLOTS_PER_WAVE + jc;
+                const int slot = wave * SLOTS_PER_WAVE + jc;
+                const int c = PACK == 1 ? slot : slot % MP;
                 if (c < m) {
-                    const char *g = base + (static_cast<int64_t>(c) * ld + row0) * ESZ;
+                    const char *g = base + (static_cast<int64_t>(c) * ld + row0 +
+                                            (PACK == 1 ? 0 : (slot / MP) * ROWS)) * ESZ;
                     if constexpr (ALIGNED) {
                         __builtin_amdgcn_global_load_lds(QN_GPTR(g + lane * 16),
-                                                         QN_LPTR(stage + c * kColPitch),
+                                                         QN_LPTR(stage + slot * kColPitch),
                                                          16, 0, /*nt*/ 2);
                     } else {
 #pragma unroll
                         for (int part = 0; part < ROWS / 64; ++part) {
                             const char *gp = g + (part * 64 + lane) * ESZ;
-                            char *lp = stage + c * kColPitch + part * 64 * LESZ;
+                            char *lp = stage + slot * kColPitch + part * 64 * LESZ;
                             if constexpr (DT == QN_F32)
                                 __builtin_amdgcn_global_load_lds(QN_GPTR(gp), QN_LPTR(lp), 4, 0, 2);
                             else
@@ -256,12 +266,13 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
         } else {
             // the ragged last tile: guarded element loads, zero fill
             for (int jc = 0; jc < SLOTS_PER_WAVE; ++jc) {
-                const int c = wave * SLOTS_PER_WAVE + jc;
+                const int slot = wave * SLOTS_PER_WAVE + jc;
+                const int c = PACK == 1 ? slot : slot % MP;
                 if (c >= m)
                     continue;
                 for (int e = 0; e < RPV; ++e) {
-                    const int64_t r = row0 + lane * RPV + e;
-                    char *dst = stage + c * kColPitch + (lane * RPV + e) * LESZ;
+                    const int64_t r = row0 + (PACK == 1 ? 0 : (slot / MP) * ROWS) + lane * RPV + e;
+                    char *dst = stage + slot * kColPitch + (lane * RPV + e) * LESZ;
                     if constexpr (DT == QN_F32) {
                         const float *src = reinterpret_cast<const float *>(base);
                         *reinterpret_cast<float *>(dst) = r < n ? src[c * ld + r] : 0.0f;
@@ -280,22 +291,22 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
             // the last wave also brings in z's rows of the tile (fp32, contiguous)
             if (wave == kGramWaves - 1) {
                 char *zl = stage + ZBASE;
-                if (row0 + ROWS <= n) {
+                if (row0 + TROWS <= n) {
                     if (z_aligned) {
 #pragma unroll
-                        for (int part = 0; part < ROWS / 256; ++part)
+                        for (int part = 0; part < TROWS / 256; ++part)
                             __builtin_amdgcn_global_load_lds(
                                 QN_GPTR(z + row0 + part * 256 + lane * 4),
                                 QN_LPTR(zl + part * 1024), 16, 0, 2);
                     } else {
 #pragma unroll
-                        for (int part = 0; part < ROWS / 64; ++part)
+                        for (int part = 0; part < TROWS / 64; ++part)
                             __builtin_amdgcn_global_load_lds(
                                 QN_GPTR(z + row0 + part * 64 + lane),
                                 QN_LPTR(zl + part * 256), 4, 0, 2);
                     }
                 } else {
-                    for (int part = 0; part < ROWS / 64; ++part) {
+                    for (int part = 0; part < TROWS / 64; ++part) {
                         const int64_t r = row0 + part * 64 + lane;
                         reinterpret_cast<float *>(zl)[part * 64 + lane] = r < n ? z[r] : 0.0f;
                     }
@@ -337,7 +348,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
             for (int sl = 0; sl < SLICES; ++sl) {
                 const char *at = stage + byte0 + sl * 8 * LESZ;
                 float x[NT][8], s[8];
-                lds_rows8<FMT>(at, s);                           // column 0: the pivot
+                lds_rows8<FMT>(at + sub * MP * kColPitch, s);    // the pivot: column 0 of this row block
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
                     lds_rows8<FMT>(at + (col + 16 * t) * kColPitch, x[t]);
@@ -345,7 +356,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
                 if constexpr (HAS_Z) {
                     // the same 8 rows of z; only the pivot lane uses them
                     float zr[8];
-                    lds_rows8<0>(stage + ZBASE + (byte0 / LESZ + sl * 8) * 4, zr);
+                    lds_rows8<0>(stage + ZBASE + (sub * ROWS + byte0 / LESZ + sl * 8) * 4, zr);
                     if (is_pivot) {
 #pragma unroll
                         for (int e = 0; e < 8; ++e)
@@ -493,18 +504,28 @@ __device__ __forceinline__ int raw_index(int k, int l)
 // C = P N P and w = P (t + N 1 / m) in fp64; one block.  z_mode: column 0 of the
 // raw matrix holds d_k^T z instead of d_k^T s, and w = G^T z = P t.
 constexpr int kProjectThreads = 1024;
+// pack > 1 (m <= 16 / pack): the raw tile holds `pack` diagonal blocks of 16 / pack
+// rows and columns, partial results for disjoint row sets, which are added.
 __global__ __launch_bounds__(kProjectThreads) void gram_project(
-    const double *__restrict__ mraw, int m, int z_mode, double *__restrict__ C,
-    double *__restrict__ w)
+    const double *__restrict__ mraw, int m, int z_mode, int pack,
+    double *__restrict__ C, double *__restrict__ w)
 {
+    const int mp = 16 / pack;        // only used when pack > 1
     __shared__ double N[QN_MAX_M][QN_MAX_M + 1];
     __shared__ double rowsum[QN_MAX_M], u[QN_MAX_M];
     __shared__ double total, umean;
     for (int e = threadIdx.x; e < m * m; e += kProjectThreads) {
         const int k = e / m, l = e % m;
         double q = 0.0;
-        if (k >= 1 && l >= 1)
-            q = (k >= l) ? mraw[raw_index(k, l)] : mraw[raw_index(l, k)];
+        if (k >= 1 && l >= 1) {
+            const int hi = k >= l ? k : l, lo = k >= l ? l : k;
+            if (pack == 1) {
+                q = mraw[raw_index(hi, lo)];
+            } else {
+                for (int b = 0; b < pack; ++b)
+                    q += mraw[raw_index(b * mp + hi, b * mp + lo)];
+            }
+        }
         N[k][l] = q;
     }
     __syncthreads();
@@ -513,7 +534,15 @@ __global__ __launch_bounds__(kProjectThreads) void gram_project(
         for (int x = 0; x < m; ++x)
             s += N[threadIdx.x][x];
         rowsum[threadIdx.x] = s;
-        const double t = threadIdx.x >= 1 ? mraw[raw_index(threadIdx.x, 0)] : 0.0;
+        double t = 0.0;
+        if (threadIdx.x >= 1) {
+            if (pack == 1) {
+                t = mraw[raw_index(threadIdx.x, 0)];
+            } else {
+                for (int b = 0; b < pack; ++b)
+                    t += mraw[raw_index(b * mp + threadIdx.x, b * mp)];
+            }
+        }
         u[threadIdx.x] = z_mode ? t : t + s / m;
     }
     __syncthreads();
@@ -535,70 +564,78 @@ __global__ __launch_bounds__(kProjectThreads) void gram_project(
         w[threadIdx.x] = u[threadIdx.x] - umean;
 }
 
-template <int DT, int NT, bool HAS_Z>
-static int launch_stage1(bool aligned, int cu_count, const void *grads, int64_t n,
-                         int m, int64_t ld, double *partials, const float *z,
-                         hipStream_t stream)
+// Blocks of one kernel instance that fit a CU: LDS (160 KiB) and 32 waves.
+constexpr int blocks_per_cu(int lds_bytes)
 {
-    const int rows = aligned ? StreamRows<DT, true>::value : StreamRows<DT, false>::value;
+    const int by_lds = 163840 / lds_bytes, by_waves = 32 / kGramWaves;
+    return by_lds < by_waves ? by_lds : by_waves;
+}
+
+template <int DT, int NT, bool AL, bool HAS_Z, int PACK>
+constexpr int instance_lds_bytes()
+{
+    return stream_lds_bytes<NT, HAS_Z ? StreamRows<DT, AL>::value * PACK / 256 : 0>();
+}
+
+template <int DT, int NT, bool AL, bool HAS_Z, int PACK>
+static int launch_instance(int cu_count, const void *grads, int64_t n, int m, int64_t ld,
+                           double *partials, const float *z, hipStream_t stream)
+{
+    constexpr int LDS = instance_lds_bytes<DT, NT, AL, HAS_Z, PACK>();
+    const int rows = StreamRows<DT, AL>::value * PACK;
     const int64_t num_tiles = (n + rows - 1) / rows;
-    int64_t cap = static_cast<int64_t>(cu_count) * stream_blocks_per_cu<NT>();
+    int64_t cap = static_cast<int64_t>(cu_count) * blocks_per_cu(LDS);
     if (cap > kGramMaxBlocks)       // the partials buffer holds this many blocks
         cap = kGramMaxBlocks;
     const int grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
     const int z_aligned = reinterpret_cast<uintptr_t>(z) % 16 == 0;
-    if (aligned) {
-        constexpr int ZS = HAS_Z ? StreamRows<DT, true>::value / 256 : 0;
-        hipLaunchKernelGGL((gram_stage1_stream<DT, NT, true, HAS_Z>), dim3(grid),
-                           dim3(kGramThreads), (stream_lds_bytes<NT, ZS>()), stream, grads, n,
-                           m, ld, partials, z, z_aligned);
-    } else {
-        constexpr int ZS = HAS_Z ? StreamRows<DT, false>::value / 256 : 0;
-        hipLaunchKernelGGL((gram_stage1_stream<DT, NT, false, HAS_Z>), dim3(grid),
-                           dim3(kGramThreads), (stream_lds_bytes<NT, ZS>()), stream, grads, n,
-                           m, ld, partials, z, z_aligned);
-    }
+    hipLaunchKernelGGL((gram_stage1_stream<DT, NT, AL, HAS_Z, PACK>), dim3(grid),
+                       dim3(kGramThreads), LDS, stream, grads, n, m, ld, partials, z, z_aligned);
     return grid;
 }
 
-template <int DT, bool HAS_Z>
-static int launch_stage1_nt(int nt, bool aligned, int cu_count, const void *grads,
-                            int64_t n, int m, int64_t ld, double *partials,
-                            const float *z, hipStream_t stream)
+// row blocks packed into the 16 column lanes of a single column set
+constexpr int pack_for(int m) { return m <= 4 ? 4 : (m <= 8 ? 2 : 1); }
+
+template <int DT, bool AL, bool HAS_Z>
+static int launch_stage1(int cu_count, const void *grads, int64_t n, int m, int64_t ld,
+                         double *partials, const float *z, hipStream_t stream)
 {
-    if (nt == 1)
-        return launch_stage1<DT, 1, HAS_Z>(aligned, cu_count, grads, n, m, ld, partials, z, stream);
-    if (nt == 2)
-        return launch_stage1<DT, 2, HAS_Z>(aligned, cu_count, grads, n, m, ld, partials, z, stream);
-    if (nt == 3)
-        return launch_stage1<DT, 3, HAS_Z>(aligned, cu_count, grads, n, m, ld, partials, z, stream);
-    return launch_stage1<DT, 4, HAS_Z>(aligned, cu_count, grads, n, m, ld, partials, z, stream);
+#define QN_GO(NTV, PK) \
+    return launch_instance<DT, NTV, AL, HAS_Z, PK>(cu_count, grads, n, m, ld, partials, z, stream)
+    if (m <= 4) QN_GO(1, 4);
+    if (m <= 8) QN_GO(1, 2);
+    if (m <= 16) QN_GO(1, 1);
+    if (m <= 32) QN_GO(2, 1);
+    if (m <= 48) QN_GO(3, 1);
+    QN_GO(4, 1);
+#undef QN_GO
 }
 
 // The streaming kernels use up to 134 KiB of dynamic LDS; the opt-in above the
 // default 64 KiB is per device and is made once when the device's workspace is
 // set up.
-template <int DT, int NT, bool AL, bool HAS_Z>
+template <int DT, int NT, bool AL, bool HAS_Z, int PACK>
 static bool opt_in_one()
 {
-    constexpr int ZS = HAS_Z ? StreamRows<DT, AL>::value / 256 : 0;
     return hipFuncSetAttribute(
-               reinterpret_cast<const void *>(gram_stage1_stream<DT, NT, AL, HAS_Z>),
+               reinterpret_cast<const void *>(gram_stage1_stream<DT, NT, AL, HAS_Z, PACK>),
                hipFuncAttributeMaxDynamicSharedMemorySize,
-               stream_lds_bytes<NT, ZS>()) == hipSuccess;
+               instance_lds_bytes<DT, NT, AL, HAS_Z, PACK>()) == hipSuccess;
 }
 
-template <int DT, int NT>
+template <int DT, int NT, int PACK>
 static bool opt_in_nt()
 {
-    return opt_in_one<DT, NT, true, false>() && opt_in_one<DT, NT, false, false>() &&
-           opt_in_one<DT, NT, true, true>() && opt_in_one<DT, NT, false, true>();
+    return opt_in_one<DT, NT, true, false, PACK>() && opt_in_one<DT, NT, false, false, PACK>() &&
+           opt_in_one<DT, NT, true, true, PACK>() && opt_in_one<DT, NT, false, true, PACK>();
 }
 
 template <int DT>
 static bool opt_in_dt()
 {
-    return opt_in_nt<DT, 1>() && opt_in_nt<DT, 2>() && opt_in_nt<DT, 3>() && opt_in_nt<DT, 4>();
+    return opt_in_nt<DT, 1, 4>() && opt_in_nt<DT, 1, 2>() && opt_in_nt<DT, 1, 1>() &&
+           opt_in_nt<DT, 2, 1>() && opt_in_nt<DT, 3, 1>() && opt_in_nt<DT, 4, 1>();
 }
 
 int setup_gram_kernels()
@@ -620,14 +657,16 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     int grid;
     {
         TraceScope ts(QN_K_GRAM, stream);
-        if (z == nullptr)
-            grid = dtype == QN_F32
-                       ? launch_stage1_nt<QN_F32, false>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, z, stream)
-                       : launch_stage1_nt<QN_BF16, false>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, z, stream);
-        else
-            grid = dtype == QN_F32
-                       ? launch_stage1_nt<QN_F32, true>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, z, stream)
-                       : launch_stage1_nt<QN_BF16, true>(nt, aligned, ws->cu_count, grads, n, m, ld, ws->partials, z, stream);
+#define QN_GO(DTV, ALV, ZV) \
+    grid = launch_stage1<DTV, ALV, ZV>(ws->cu_count, grads, n, m, ld, ws->partials, z, stream)
+        if (dtype == QN_F32) {
+            if (aligned) { if (z) QN_GO(QN_F32, true, true); else QN_GO(QN_F32, true, false); }
+            else { if (z) QN_GO(QN_F32, false, true); else QN_GO(QN_F32, false, false); }
+        } else {
+            if (aligned) { if (z) QN_GO(QN_BF16, true, true); else QN_GO(QN_BF16, true, false); }
+            else { if (z) QN_GO(QN_BF16, false, true); else QN_GO(QN_BF16, false, false); }
+        }
+#undef QN_GO
     }
     if (check_launch() != QN_OK) return QN_ELAUNCH;
     {
@@ -639,7 +678,7 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     {
         TraceScope ts(QN_K_PROJECT, stream);
         hipLaunchKernelGGL(gram_project, dim3(1), dim3(kProjectThreads), 0, stream,
-                           ws->mraw, m, z != nullptr ? 1 : 0, C, w);
+                           ws->mraw, m, z != nullptr ? 1 : 0, pack_for(m), C, w);
     }
     return check_launch();
 }

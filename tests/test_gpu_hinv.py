@@ -140,7 +140,8 @@ def test_hinv_j0_and_nonfinite():
 
 @pytest.mark.parametrize("name,n,m", [("gpt2_small", 33_000, 32), ("gpt2_small", 9_001, 64),
                                       ("stress_1b_bf16", 20_480, 32), ("stress_1b_bf16", 7_777, 12),
-                                      ("small_mlp", 300, 8)])
+                                      ("small_mlp", 300, 8), ("gpt2_small", 50_000, 4),
+                                      ("stress_1b_bf16", 30_000, 8), ("stress_1b_bf16", 9_000, 3)])
 def test_z_at_any_alignment_gives_the_same_bits(name, n, m):
     # z rides through the Gram pass in its own LDS slot, fetched with 16-byte or
     # 4-byte direct-to-LDS loads depending on its address: same values, same bits

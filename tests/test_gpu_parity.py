@@ -62,6 +62,10 @@ GRAM_CASES = [
     ("gpt2_small", 60000, 64), ("gpt2_small", 30001, 33), ("resnet50", 20480, 48),
     ("stress_1b_bf16", 40000, 64), ("stress_1b_bf16", 20003, 47),
     ("gpt2_small", 20001, 64), ("stress_1b_bf16", 10001, 64),      # unaligned columns, four sets
+    # few workers at larger n: row blocks packed side by side in the column lanes
+    ("gpt2_small", 100_000, 8), ("gpt2_small", 70_001, 4), ("gpt2_small", 50_000, 2),
+    ("gpt2_small", 30_000, 5), ("stress_1b_bf16", 50_000, 5), ("stress_1b_bf16", 40_001, 3),
+    ("stress_1b_bf16", 65_536, 8),
 ]
 
 
