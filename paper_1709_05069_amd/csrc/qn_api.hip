@@ -36,7 +36,7 @@ int get_workspace(Workspace **out)
         Workspace ws{};
         ws.cu_count = prop.multiProcessorCount;
         const size_t b_part = align_up(sizeof(double) * kGramMaxBlocks * kMaxEntries, 256);
-        const size_t b_mraw = align_up(sizeof(double) * kMaxEntries, 256);
+        const size_t b_mraw = align_up(sizeof(double) * kReduceRows * kMaxEntries, 256);
         const size_t b_C = align_up(sizeof(double) * QN_MAX_M * QN_MAX_M, 256);
         const size_t b_w = align_up(sizeof(double) * QN_MAX_M, 256);
         const size_t b_c = align_up(sizeof(float) * QN_MAX_M, 256);

@@ -456,29 +456,32 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     }
 }
 
-// Fixed-order fp64 sum over the block partials.  Block b owns 64 entries; 16
-// slices of partials are summed serially per thread, then in slice order.
+// Fixed-order fp64 sum over the block partials in two levels.  Block (b, r) owns
+// 64 entries and the partials p = r*16 + slice (mod 16 * kReduceRows): each of its
+// 16 thread slices sums its partials serially, the slices are added in order,
+// and row r of mraw receives the result; gram_project adds the rows in order.
 constexpr int kReduceSlices = 16;
 __global__ __launch_bounds__(64 * kReduceSlices) void gram_reduce(
     const double *__restrict__ partials, int num_partials, int entries,
     double *__restrict__ mraw)
 {
     __shared__ double part[kReduceSlices][64];
+    constexpr int STRIDE = kReduceSlices * kReduceRows;
     const int e = blockIdx.x * 64 + (threadIdx.x & 63);
     const int slice = threadIdx.x >> 6;
-    // eight loads in flight, added in the order of p (the order fixes the bits)
+    // up to eight loads in flight, added in the order of p (the order fixes the bits)
     double s = 0.0;
-    int p = slice;
-    for (; p + 7 * kReduceSlices < num_partials; p += 8 * kReduceSlices) {
+    int p = blockIdx.y * kReduceSlices + slice;
+    for (; p + 7 * STRIDE < num_partials; p += 8 * STRIDE) {
         double v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            v[u] = partials[static_cast<int64_t>(p + u * kReduceSlices) * entries + e];
+            v[u] = partials[static_cast<int64_t>(p + u * STRIDE) * entries + e];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
             s += v[u];
     }
-    for (; p < num_partials; p += kReduceSlices)
+    for (; p < num_partials; p += STRIDE)
         s += partials[static_cast<int64_t>(p) * entries + e];
     part[slice][threadIdx.x & 63] = s;
     __syncthreads();
@@ -487,7 +490,7 @@ __global__ __launch_bounds__(64 * kReduceSlices) void gram_reduce(
 #pragma unroll
         for (int k = 0; k < kReduceSlices; ++k)
             r += part[k][threadIdx.x];
-        mraw[e] = r;
+        mraw[static_cast<int64_t>(blockIdx.y) * entries + e] = r;
     }
 }
 
@@ -507,10 +510,18 @@ constexpr int kProjectThreads = 1024;
 // pack > 1 (m <= 16 / pack): the raw tile holds `pack` diagonal blocks of 16 / pack
 // rows and columns, partial results for disjoint row sets, which are added.
 __global__ __launch_bounds__(kProjectThreads) void gram_project(
-    const double *__restrict__ mraw, int m, int z_mode, int pack,
+    const double *__restrict__ mraw, int entries, int m, int z_mode, int pack,
     double *__restrict__ C, double *__restrict__ w)
 {
     const int mp = 16 / pack;        // only used when pack > 1
+    // Q[k][l], k >= l: the rows of the two-level reduction added in order
+    auto raw = [&](int k, int l) {
+        const int at = raw_index(k, l);
+        double q = 0.0;
+        for (int r = 0; r < kReduceRows; ++r)
+            q += mraw[r * entries + at];
+        return q;
+    };
     __shared__ double N[QN_MAX_M][QN_MAX_M + 1];
     __shared__ double rowsum[QN_MAX_M], u[QN_MAX_M];
     __shared__ double total, umean;
@@ -520,10 +531,10 @@ __global__ __launch_bounds__(kProjectThreads) void gram_project(
         if (k >= 1 && l >= 1) {
             const int hi = k >= l ? k : l, lo = k >= l ? l : k;
             if (pack == 1) {
-                q = mraw[raw_index(hi, lo)];
+                q = raw(hi, lo);
             } else {
                 for (int b = 0; b < pack; ++b)
-                    q += mraw[raw_index(b * mp + hi, b * mp + lo)];
+                    q += raw(b * mp + hi, b * mp + lo);
             }
         }
         N[k][l] = q;
@@ -537,10 +548,10 @@ __global__ __launch_bounds__(kProjectThreads) void gram_project(
         double t = 0.0;
         if (threadIdx.x >= 1) {
             if (pack == 1) {
-                t = mraw[raw_index(threadIdx.x, 0)];
+                t = raw(threadIdx.x, 0);
             } else {
                 for (int b = 0; b < pack; ++b)
-                    t += mraw[raw_index(b * mp + threadIdx.x, b * mp)];
+                    t += raw(b * mp + threadIdx.x, b * mp);
             }
         }
         u[threadIdx.x] = z_mode ? t : t + s / m;
@@ -671,14 +682,15 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     if (check_launch() != QN_OK) return QN_ELAUNCH;
     {
         TraceScope ts(QN_K_REDUCE, stream);
-        hipLaunchKernelGGL(gram_reduce, dim3(entries / 64), dim3(64 * kReduceSlices), 0,
-                           stream, ws->partials, grid, entries, ws->mraw);
+        hipLaunchKernelGGL(gram_reduce, dim3(entries / 64, kReduceRows),
+                           dim3(64 * kReduceSlices), 0, stream, ws->partials, grid, entries,
+                           ws->mraw);
     }
     if (check_launch() != QN_OK) return QN_ELAUNCH;
     {
         TraceScope ts(QN_K_PROJECT, stream);
         hipLaunchKernelGGL(gram_project, dim3(1), dim3(kProjectThreads), 0, stream,
-                           ws->mraw, m, z != nullptr ? 1 : 0, pack_for(m), C, w);
+                           ws->mraw, entries, m, z != nullptr ? 1 : 0, pack_for(m), C, w);
     }
     return check_launch();
 }

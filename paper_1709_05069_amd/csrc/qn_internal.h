@@ -23,11 +23,12 @@ constexpr int kGramMaxBlocks = 1024;
 constexpr int kTileEntries = 256;               // 16 x 16
 constexpr int kMaxTiles = 10;                   // lower triangle of a 4x4 tiling (m <= 64)
 constexpr int kMaxEntries = kTileEntries * kMaxTiles;
+constexpr int kReduceRows = 8;                  // rows of the two-level partial reduction
 
 // ---- per-device workspace ---------------------------------------------------
 struct Workspace {
     double *partials;   // kGramMaxBlocks * kMaxEntries
-    double *mraw;       // kMaxEntries: reduced accumulators, raw tile layout
+    double *mraw;       // kReduceRows * kMaxEntries: reduced accumulators, raw tile layout
     double *C;          // QN_MAX_M * QN_MAX_M
     double *w;          // QN_MAX_M
     float *c;           // QN_MAX_M
