@@ -203,10 +203,11 @@ int qn_update_ex(const void *thetas, const void *grads, int dtype, int64_t n,
     if (rc != QN_OK)
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = launch_gram(grads, dtype, n, m, ld, ws, nullptr, ws->C, ws->w, s);
+    RawGram raw;
+    rc = launch_gram_raw(grads, dtype, n, m, ld, ws, nullptr, &raw, s);
     if (rc != QN_OK)
         return rc;
-    rc = launch_eig(ws->C, ws->w, m, lambda, nullptr, nullptr, ws->c, j_out, s);
+    rc = launch_eig(nullptr, nullptr, m, lambda, nullptr, nullptr, ws->c, j_out, s, &raw);
     if (rc != QN_OK)
         return rc;
     return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, nullptr, tau, nullptr, theta_new,

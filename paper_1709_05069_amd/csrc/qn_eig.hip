@@ -18,6 +18,7 @@
 // refined by Newton steps to full double precision; the matrix is pre-scaled by
 // a power of two so that squares cannot overflow or vanish.
 #include "qn_internal.h"
+#include "qn_project.h"
 
 namespace qn {
 
@@ -98,11 +99,15 @@ __device__ __forceinline__ void rotation(double app, double aqq, double apq,
     }
 }
 
+// Input: C and w in memory, or (C == nullptr) the raw accumulators of the Gram
+// pass, from which the kernel forms C and w itself (qn_project.h), saving the
+// launch of gram_project inside the fused entry points.
 template <int M>
 __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
     const double *__restrict__ C, const double *__restrict__ w, int m,
     double lambda, double *__restrict__ sigma_out, double *__restrict__ V_out,
-    float *__restrict__ c_out, int *__restrict__ j_out)
+    float *__restrict__ c_out, int *__restrict__ j_out,
+    const double *__restrict__ mraw, int entries, int z_mode, int pack)
 {
     constexpr int NP = M / 2;          // pairs per round
     constexpr int ROUNDS = M - 1;
@@ -125,12 +130,21 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
     __syncthreads();
 
     // symmetric part, zero padding, V = I, non-finite scan, schedule
+    if (C == nullptr) {
+        // from the raw accumulators: C lands in A[0], w in wv; the second copy of
+        // the matrix is free to serve as the projection's work space
+        __shared__ ProjectScratch sc;
+        project_raw<kEigThreads>(
+            mraw, entries, m, z_mode, pack, &A[1][0][0], LD, sc,
+            [&](int k, int l, double v) { A[0][k][l] = v; },
+            [&](int k, double v) { wv[k] = v; });
+    }
     double amax = 0.0;
     for (int e = tid; e < M * M; e += kEigThreads) {
         const int k = e / M, l = e % M;
         double v = 0.0;
         if (k < m && l < m) {
-            v = 0.5 * (C[l * m + k] + C[k * m + l]);
+            v = C != nullptr ? 0.5 * (C[l * m + k] + C[k * m + l]) : A[0][k][l];
             if (!isfinite(v))
                 bad = 1;
             amax = fmax(amax, fabs(v));
@@ -139,7 +153,8 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
         V[k][l] = (k == l) ? 1.0 : 0.0;
     }
     if (tid < m) {
-        wv[tid] = w[tid];
+        if (C != nullptr)
+            wv[tid] = w[tid];
         if (!isfinite(wv[tid]))
             bad = 1;
     }
@@ -307,13 +322,21 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
 
 int launch_eig(const double *C, const double *w, int m, float lambda,
                double *sigma, double *V, float *c, int *j_out,
-               hipStream_t stream)
+               hipStream_t stream, const RawGram *raw)
 {
+    const double *mraw = raw ? raw->mraw : nullptr;
+    const int entries = raw ? raw->entries : 0, z_mode = raw ? raw->z_mode : 0,
+              pack = raw ? raw->pack : 1;
+    if (raw) {
+        C = nullptr;
+        w = nullptr;
+    }
     TraceScope ts(QN_K_EIG, stream);
     const double lam = static_cast<double>(lambda);
 #define QN_EIG_LAUNCH(MM)                                                            \
     hipLaunchKernelGGL(eig_select<MM>, dim3(1), dim3(eig_threads<MM>()),             \
-                       eig_lds_bytes<MM>(), stream, C, w, m, lam, sigma, V, c, j_out)
+                       eig_lds_bytes<MM>(), stream, C, w, m, lam, sigma, V, c, j_out,   \
+                       mraw, entries, z_mode, pack)
     if (m <= 2) QN_EIG_LAUNCH(2);
     else if (m <= 4) QN_EIG_LAUNCH(4);
     else if (m <= 8) QN_EIG_LAUNCH(8);

@@ -43,6 +43,7 @@
 // Stage 2 (gram_reduce): fixed-order fp64 sum of the block partials.
 // Stage 3 (gram_project): the m x m algebra above.
 #include "qn_internal.h"
+#include "qn_project.h"
 
 namespace qn {
 
@@ -57,7 +58,6 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 // NT column sets of 16: lower-triangle tiles, tile (ti, tj), ti >= tj, at index
 // ti (ti + 1) / 2 + tj.
 template <int NT> struct GramTiles { static constexpr int value = NT * (NT + 1) / 2; };
-__host__ __device__ constexpr int tile_index(int ti, int tj) { return ti * (ti + 1) / 2 + tj; }
 
 // ---------------------------------------------------------------------------
 // A tile is ROWS rows of all columns; a column's rows of one tile are 1 KiB in
@@ -494,85 +494,20 @@ __global__ __launch_bounds__(64 * kReduceSlices) void gram_reduce(
     }
 }
 
-// Position of Q[k][l] (k >= l) in the raw accumulator layout: tile (k/16, l/16)
-// of the lower triangle, and inside a tile element (i, j) sits in register i%4
-// of lane 16*(i/4) + j.
-__device__ __forceinline__ int raw_index(int k, int l)
-{
-    const int tile = tile_index(k >> 4, l >> 4);
-    const int i = k & 15, j = l & 15;
-    return (tile * 4 + (i & 3)) * 64 + (i >> 2) * 16 + j;
-}
-
-// C = P N P and w = P (t + N 1 / m) in fp64; one block.  z_mode: column 0 of the
-// raw matrix holds d_k^T z instead of d_k^T s, and w = G^T z = P t.
+// C = P N P and w = P (t + N 1 / m) in fp64; one block (the algebra is in
+// qn_project.h).  z_mode: column 0 of the raw matrix holds d_k^T z instead of
+// d_k^T s, and w = G^T z = P t.
 constexpr int kProjectThreads = 1024;
-// pack > 1 (m <= 16 / pack): the raw tile holds `pack` diagonal blocks of 16 / pack
-// rows and columns, partial results for disjoint row sets, which are added.
 __global__ __launch_bounds__(kProjectThreads) void gram_project(
     const double *__restrict__ mraw, int entries, int m, int z_mode, int pack,
     double *__restrict__ C, double *__restrict__ w)
 {
-    const int mp = 16 / pack;        // only used when pack > 1
-    // Q[k][l], k >= l: the rows of the two-level reduction added in order
-    auto raw = [&](int k, int l) {
-        const int at = raw_index(k, l);
-        double q = 0.0;
-        for (int r = 0; r < kReduceRows; ++r)
-            q += mraw[r * entries + at];
-        return q;
-    };
-    __shared__ double N[QN_MAX_M][QN_MAX_M + 1];
-    __shared__ double rowsum[QN_MAX_M], u[QN_MAX_M];
-    __shared__ double total, umean;
-    for (int e = threadIdx.x; e < m * m; e += kProjectThreads) {
-        const int k = e / m, l = e % m;
-        double q = 0.0;
-        if (k >= 1 && l >= 1) {
-            const int hi = k >= l ? k : l, lo = k >= l ? l : k;
-            if (pack == 1) {
-                q = raw(hi, lo);
-            } else {
-                for (int b = 0; b < pack; ++b)
-                    q += raw(b * mp + hi, b * mp + lo);
-            }
-        }
-        N[k][l] = q;
-    }
-    __syncthreads();
-    if (threadIdx.x < m) {
-        double s = 0.0;
-        for (int x = 0; x < m; ++x)
-            s += N[threadIdx.x][x];
-        rowsum[threadIdx.x] = s;
-        double t = 0.0;
-        if (threadIdx.x >= 1) {
-            if (pack == 1) {
-                t = raw(threadIdx.x, 0);
-            } else {
-                for (int b = 0; b < pack; ++b)
-                    t += raw(b * mp + threadIdx.x, b * mp);
-            }
-        }
-        u[threadIdx.x] = z_mode ? t : t + s / m;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double s = 0.0, su = 0.0;
-        for (int x = 0; x < m; ++x) {
-            s += rowsum[x];
-            su += u[x];
-        }
-        total = s;
-        umean = su / m;
-    }
-    __syncthreads();
-    for (int e = threadIdx.x; e < m * m; e += kProjectThreads) {
-        const int k = e / m, l = e % m;
-        C[l * m + k] = N[k][l] - (rowsum[k] + rowsum[l]) / m + total / (static_cast<double>(m) * m);
-    }
-    if (threadIdx.x < m)
-        w[threadIdx.x] = u[threadIdx.x] - umean;
+    __shared__ double N[QN_MAX_M * (QN_MAX_M + 1)];
+    __shared__ ProjectScratch sc;
+    project_raw<kProjectThreads>(
+        mraw, entries, m, z_mode, pack, N, QN_MAX_M + 1, sc,
+        [&](int k, int l, double v) { C[l * m + k] = v; },
+        [&](int k, double v) { w[k] = v; });
 }
 
 // Blocks of one kernel instance that fit a CU: LDS (160 KiB) and 32 waves.
@@ -654,8 +589,8 @@ int setup_gram_kernels()
     return opt_in_dt<QN_F32>() && opt_in_dt<QN_BF16>() ? QN_OK : QN_ELAUNCH;
 }
 
-int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
-                Workspace *ws, const float *z, double *C, double *w, hipStream_t stream)
+int launch_gram_raw(const void *grads, int dtype, int64_t n, int m, int64_t ld,
+                    Workspace *ws, const float *z, RawGram *raw, hipStream_t stream)
 {
     const size_t esz = dtype == QN_F32 ? 4 : 2;
     const bool aligned = (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
@@ -686,12 +621,23 @@ int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
                            dim3(64 * kReduceSlices), 0, stream, ws->partials, grid, entries,
                            ws->mraw);
     }
-    if (check_launch() != QN_OK) return QN_ELAUNCH;
-    {
-        TraceScope ts(QN_K_PROJECT, stream);
-        hipLaunchKernelGGL(gram_project, dim3(1), dim3(kProjectThreads), 0, stream,
-                           ws->mraw, entries, m, z != nullptr ? 1 : 0, pack_for(m), C, w);
-    }
+    raw->mraw = ws->mraw;
+    raw->entries = entries;
+    raw->z_mode = z != nullptr ? 1 : 0;
+    raw->pack = pack_for(m);
+    return check_launch();
+}
+
+int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
+                Workspace *ws, const float *z, double *C, double *w, hipStream_t stream)
+{
+    RawGram raw;
+    const int rc = launch_gram_raw(grads, dtype, n, m, ld, ws, z, &raw, stream);
+    if (rc != QN_OK)
+        return rc;
+    TraceScope ts(QN_K_PROJECT, stream);
+    hipLaunchKernelGGL(gram_project, dim3(1), dim3(kProjectThreads), 0, stream, raw.mraw,
+                       raw.entries, m, raw.z_mode, raw.pack, C, w);
     return check_launch();
 }
 

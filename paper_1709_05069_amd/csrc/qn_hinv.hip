@@ -120,10 +120,11 @@ int qn_hinv_ex(const void *thetas, const void *grads, int dtype, const float *z,
     if (rc != QN_OK)
         return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    rc = launch_gram(grads, dtype, n, m, ld, ws, z, ws->C, ws->wz, s);
+    RawGram raw;
+    rc = launch_gram_raw(grads, dtype, n, m, ld, ws, z, &raw, s);
     if (rc != QN_OK)
         return rc;
-    rc = launch_eig(ws->C, ws->wz, m, lambda, nullptr, nullptr, ws->cz, j_out, s);
+    rc = launch_eig(nullptr, nullptr, m, lambda, nullptr, nullptr, ws->cz, j_out, s, &raw);
     if (rc != QN_OK)
         return rc;
     return launch_apply(thetas, grads, dtype, n, m, ld, ws->cz, z, 0.0f, nullptr, out,

@@ -56,9 +56,21 @@ int setup_eig_kernels();
 // C = G^T G and, with z == nullptr, w = G^T g_bar; with z (n fp32 values) w = G^T z
 int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
                 Workspace *ws, const float *z, double *C, double *w, hipStream_t stream);
+// The raw, pivot-shifted accumulators of a Gram pass (kReduceRows rows of
+// `entries` doubles in the workspace) and what is needed to decode them.
+struct RawGram {
+    const double *mraw;
+    int entries;
+    int z_mode;     // column 0 holds d_k^T z rather than d_k^T s
+    int pack;       // row blocks packed into the single column set (m <= 8)
+};
+// stage 1 + reduce only; launch_gram adds the projection to C and w
+int launch_gram_raw(const void *grads, int dtype, int64_t n, int m, int64_t ld,
+                    Workspace *ws, const float *z, RawGram *raw, hipStream_t stream);
+// raw != nullptr: C and w are formed inside the kernel from the raw accumulators
 int launch_eig(const double *C, const double *w, int m, float lambda,
                double *sigma, double *V, float *c, int *j_out,
-               hipStream_t stream);
+               hipStream_t stream, const RawGram *raw = nullptr);
 // z == nullptr: theta_new = theta_bar - tau (g_bar + (Theta - G) c);
 // z != nullptr: theta_new = z + (Theta - G) c  (tau unused);
 // tau_dev != nullptr: tau is read from device memory instead of the argument

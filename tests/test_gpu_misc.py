@@ -25,7 +25,9 @@ def test_trace_counts_every_kernel_once_per_update():
     tr = qn.trace_end()
     assert set(tr) == set(qn.KERNEL_NAMES)
     for name, (ms, cnt) in tr.items():
-        if name in ("coef", "tau_bound"):   # the general-z operator, the capped step
+        # the pieces' projection kernel (the fused step projects inside the eigen
+        # kernel), the coefficient piece, the capped step
+        if name in ("gram_project", "coef", "tau_bound"):
             assert cnt == 0
         else:
             assert cnt == 3 and ms > 0.0
