@@ -21,8 +21,9 @@
 //   operands agree.  The m columns form NT = 1..4 sets of 16 (m <= 16, 32, 48, 64)
 //   and only the lower triangle of the NT x NT tiling is computed (1, 3, 6 or 10
 //   tiles).  For m <= 8 (<= 4) two (four) row blocks of the same columns share
-//   the 16 column lanes of the single set.  The shifted fp32 entry is split into bf16 terms whose products the
-//   matrix cores form exactly and accumulate in fp32:
+//   the 16 column lanes of the single set.  The shifted fp32 entry is split into
+//   bf16 terms whose products the matrix cores form exactly and accumulate in
+//   fp32:
 //     fp32 storage: d = hi + mid + lo exactly (8 + 8 + 8 significant bits, by
 //       truncation); six products (all but mid lo, lo mid, lo lo, which are below
 //       2^-23 of the leading one).  This is both more accurate than fp32
@@ -40,8 +41,9 @@
 //   block; the wavefronts then read their operands from LDS in the lane = column
 //   layout.  Measured on MI355X this load pattern sustains about 7.0 TB/s,
 //   against 6.4 TB/s when each lane fetches its own column straight from HBM.
-// Stage 2 (gram_reduce): fixed-order fp64 sum of the block partials.
-// Stage 3 (gram_project): the m x m algebra above.
+// Stage 2 (gram_reduce): fixed-order fp64 sum of the block partials, two levels.
+// Stage 3 (gram_project, or the prologue of the eigen kernel): the m x m algebra
+//   above (qn_project.h).
 #include "qn_internal.h"
 #include "qn_project.h"
 
@@ -60,16 +62,16 @@ typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
 template <int NT> struct GramTiles { static constexpr int value = NT * (NT + 1) / 2; };
 
 // ---------------------------------------------------------------------------
-// A tile is ROWS rows of all columns; a column's rows of one tile are 1 KiB in
-// LDS at slot * kColPitch (1 KiB + 16 B, which spreads the 16 columns a
-// quarter-wave reads over all banks).  16 * NT slots per stage, two stages.
+// A column slot is 1 KiB of one column (ROWS rows) at slot * kColPitch in LDS
+// (1 KiB + 16 B, which spreads the 16 columns a quarter-wave reads over all
+// banks).  16 * NT slots per stage, two stages.
 constexpr int kColPitch = 1040;                       // bytes per column slot
 // A pass that also carries a vector z (below) keeps z's rows of the tile in
 // ZSLOTS further slots of each stage (fp32: 1 KiB per 256 rows).
 template <int NT, int ZSLOTS> constexpr int stage_bytes() { return (16 * NT + ZSLOTS) * kColPitch; }
 template <int NT, int ZSLOTS> constexpr int stream_lds_bytes() { return 2 * stage_bytes<NT, ZSLOTS>(); }
 
-// Rows per tile.  bf16 inputs that are not 16-byte aligned arrive through
+// Rows per column slot.  bf16 inputs that are not 16-byte aligned arrive through
 // 2-byte direct-to-LDS loads, which the hardware stores zero-extended, one per
 // dword: their LDS format is 4 bytes per row.
 template <int DT, bool ALIGNED> struct StreamRows {
