@@ -3,8 +3,8 @@
 //
 // One workgroup, everything in LDS, fp64 throughout.  The solver is the
 // parallel-order two-sided Jacobi method.  The matrix is padded to M = 2, 4, 8,
-// 16, 24, 32, 48 or 64 (inert zero rows/columns); the block has 256 threads up
-// to M = 32 and 1024 above.  The M indices are paired by a
+// 16, 24, 32, 48 or 64 (inert zero rows/columns); the block has 256 threads (512
+// at M = 48), each taking one or several of the (M/2)^2 blocks of a round.  The M indices are paired by a
 // round-robin tournament: M/2 disjoint pairs per round, M-1 rounds per sweep,
 // the schedule tabulated once in LDS.  One round costs one barrier:
 //   * every wavefront computes all M/2 plane rotations redundantly (lane l owns
@@ -23,7 +23,10 @@
 namespace qn {
 
 constexpr int kEigMaxSweeps = 30;
-template <int M> constexpr int eig_threads() { return M <= 32 ? 256 : 1024; }   // >= (M/2)^2, a power of two
+// A power of two (the block reductions are trees).  Above M = 32 a thread takes
+// several of the (M/2)^2 blocks of a round; measured best: 512 threads at M = 48
+// (359 us against 384 with 1024), 256 at M = 64 (709 us against 832 with 1024).
+template <int M> constexpr int eig_threads() { return M == 48 ? 512 : 256; }
 // dynamic LDS: two copies of the matrix and the eigenvectors, leading dimension M + 1
 template <int M> constexpr int eig_lds_bytes() { return 3 * M * (M + 1) * static_cast<int>(sizeof(double)); }
 
@@ -203,8 +206,8 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
     const double tol2 = 1e-28 * block_sum<kEigThreads>(tot, scratch);
 
     int cur = 0;
-    const bool active = tid < NP * NP;
-    const int pa = tid / NP, pb = tid % NP;      // this thread's pair indices
+    // the NP x NP blocks (pair a) x (pair b) are dealt out BPT per thread
+    constexpr int BPT = (NP * NP + kEigThreads - 1) / kEigThreads;
     for (int sweep = 0; sweep < kEigMaxSweeps; ++sweep) {
         double off = 0.0;
         for (int e = tid; e < M * M; e += kEigThreads) {
@@ -221,33 +224,39 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
             const int rp = sp[round][pr], rq = sq[round][pr];
             double rc, rs;
             rotation(A[cur][rp][rp], A[cur][rq][rq], A[cur][rp][rq], rc, rs);
-            const double c1 = __shfl(rc, pa), s1 = __shfl(rs, pa);
-            const double c2 = __shfl(rc, pb), s2 = __shfl(rs, pb);
-            if (active) {
-                const int p1 = sp[round][pa], q1 = sq[round][pa];
-                const int p2 = sp[round][pb], q2 = sq[round][pb];
-                const double b00 = A[cur][p1][p2], b01 = A[cur][p1][q2];
-                const double b10 = A[cur][q1][p2], b11 = A[cur][q1][q2];
-                // V <- V J_a on rows 2*pb, 2*pb + 1
-                const double vp0 = V[p1][2 * pb], vq0 = V[q1][2 * pb];
-                const double vp1 = V[p1][2 * pb + 1], vq1 = V[q1][2 * pb + 1];
-                // B <- J_a^T B J_b
-                const double t00 = c1 * b00 - s1 * b10, t01 = c1 * b01 - s1 * b11;
-                const double t10 = s1 * b00 + c1 * b10, t11 = s1 * b01 + c1 * b11;
-                double n00 = c2 * t00 - s2 * t01, n01 = s2 * t00 + c2 * t01;
-                double n10 = c2 * t10 - s2 * t11, n11 = s2 * t10 + c2 * t11;
-                if (pa == pb) {   // the annihilated pair: exactly diagonal
-                    n01 = 0.0;
-                    n10 = 0.0;
+#pragma unroll
+            for (int i = 0; i < BPT; ++i) {
+                const int blk = tid + i * kEigThreads;
+                const int pa = blk / NP, pb = blk % NP;      // this block's pair indices
+                // pa < NP also for the idle tail, so the shuffles stay in range
+                const double c1 = __shfl(rc, pa % NP), s1 = __shfl(rs, pa % NP);
+                const double c2 = __shfl(rc, pb), s2 = __shfl(rs, pb);
+                if (blk < NP * NP) {
+                    const int p1 = sp[round][pa], q1 = sq[round][pa];
+                    const int p2 = sp[round][pb], q2 = sq[round][pb];
+                    const double b00 = A[cur][p1][p2], b01 = A[cur][p1][q2];
+                    const double b10 = A[cur][q1][p2], b11 = A[cur][q1][q2];
+                    // V <- V J_a on rows 2*pb, 2*pb + 1
+                    const double vp0 = V[p1][2 * pb], vq0 = V[q1][2 * pb];
+                    const double vp1 = V[p1][2 * pb + 1], vq1 = V[q1][2 * pb + 1];
+                    // B <- J_a^T B J_b
+                    const double t00 = c1 * b00 - s1 * b10, t01 = c1 * b01 - s1 * b11;
+                    const double t10 = s1 * b00 + c1 * b10, t11 = s1 * b01 + c1 * b11;
+                    double n00 = c2 * t00 - s2 * t01, n01 = s2 * t00 + c2 * t01;
+                    double n10 = c2 * t10 - s2 * t11, n11 = s2 * t10 + c2 * t11;
+                    if (pa == pb) {   // the annihilated pair: exactly diagonal
+                        n01 = 0.0;
+                        n10 = 0.0;
+                    }
+                    A[cur ^ 1][p1][p2] = n00;
+                    A[cur ^ 1][p1][q2] = n01;
+                    A[cur ^ 1][q1][p2] = n10;
+                    A[cur ^ 1][q1][q2] = n11;
+                    V[p1][2 * pb] = c1 * vp0 - s1 * vq0;
+                    V[q1][2 * pb] = s1 * vp0 + c1 * vq0;
+                    V[p1][2 * pb + 1] = c1 * vp1 - s1 * vq1;
+                    V[q1][2 * pb + 1] = s1 * vp1 + c1 * vq1;
                 }
-                A[cur ^ 1][p1][p2] = n00;
-                A[cur ^ 1][p1][q2] = n01;
-                A[cur ^ 1][q1][p2] = n10;
-                A[cur ^ 1][q1][q2] = n11;
-                V[p1][2 * pb] = c1 * vp0 - s1 * vq0;
-                V[q1][2 * pb] = s1 * vp0 + c1 * vq0;
-                V[p1][2 * pb + 1] = c1 * vp1 - s1 * vq1;
-                V[q1][2 * pb + 1] = s1 * vp1 + c1 * vq1;
             }
             __syncthreads();
             cur ^= 1;
