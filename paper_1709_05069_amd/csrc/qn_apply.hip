@@ -41,6 +41,11 @@ constexpr int kApplyThreads = 256;
 #ifndef QN_APPLY_CHUNK_BF16
 #define QN_APPLY_CHUNK_BF16 2
 #endif
+// bf16 storage: accumulate the stored values themselves instead of differences
+// to the pivot (see compute_rows)
+#ifndef QN_APPLY_BF16_RAW
+#define QN_APPLY_BF16_RAW 1
+#endif
 template <int DT> struct ApplyChunk {
     static constexpr int value = DT == QN_F32 ? QN_APPLY_CHUNK_F32 : QN_APPLY_CHUNK_BF16;
 };
@@ -74,6 +79,54 @@ __device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (
     }
 }
 
+// The same load kept as it arrives (16 bytes, or one element), and its unpacking
+// to fp32.  The pipelined loop below carries loads across iterations in this
+// form: unpacking bf16 at load time would make every iteration wait for the
+// loads it has just issued.
+template <int DT, int R> struct RawRows {
+    using type = v4u;           // R == 4 fp32 values or R == 8 bf16 values
+};
+template <> struct RawRows<QN_F32, 1> { using type = float; };
+template <> struct RawRows<QN_BF16, 1> { using type = uint16_t; };
+
+template <int DT, int R>
+__device__ __forceinline__ typename RawRows<DT, R>::type load_raw(const void *base, int64_t elem)
+{
+    if constexpr (R == 1) {
+        return static_cast<const typename RawRows<DT, 1>::type *>(base)[elem];
+    } else {
+        const char *p = static_cast<const char *>(base) + elem * (DT == QN_F32 ? 4 : 2);
+        if constexpr (DT == QN_F32)
+            return __builtin_bit_cast(v4u, __builtin_nontemporal_load(reinterpret_cast<const v4f_elem *>(p)));
+        else
+            return __builtin_nontemporal_load(reinterpret_cast<const v4u_elem *>(p));
+    }
+}
+
+template <int DT, int R>
+__device__ __forceinline__ void unpack_rows(const typename RawRows<DT, R>::type &v, float (&x)[R])
+{
+    if constexpr (R == 1) {
+        if constexpr (DT == QN_F32)
+            x[0] = v;
+        else
+            x[0] = __uint_as_float(static_cast<uint32_t>(v) << 16);
+    } else {
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+        if constexpr (DT == QN_F32) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                x[e] = __uint_as_float(u[e]);
+        } else {
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                x[2 * h + 0] = __uint_as_float(u[h] << 16);
+                x[2 * h + 1] = __uint_as_float(u[h] & 0xffff0000u);
+            }
+        }
+    }
+}
+
 // theta_new for rows [row, row + R), from every worker column.
 template <int DT, int MC, int R>
 __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
@@ -85,57 +138,66 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
                                              float (&res)[R])
 {
     constexpr int kApplyChunk = ApplyChunk<DT>::value;
+    // bf16 storage: the inputs carry 8 significant bits, so plain fp32 sums of the
+    // stored values (St = sum theta_k, acc = sum c_k (theta_k - g_k), error about
+    // 1e-7 of the values) are far inside the data's own resolution and save a
+    // third of the arithmetic, which this path is short of (twice the elements
+    // per byte).  fp32 storage keeps the pivot form.
+    constexpr bool RAW = DT == QN_BF16 && QN_APPLY_BF16_RAW;
     const int m = MC ? MC : m_rt;
     float p[R], r[R], st[R], sh[R], acc[R];
     load_vec<DT, R>(thetas, row, p);
     load_vec<DT, R>(grads, row, r);
+    const float c0 = RAW ? c[0] : 0.0f;
 #pragma unroll
     for (int e = 0; e < R; ++e) {
-        st[e] = 0.0f;
-        sh[e] = 0.0f;
-        acc[e] = 0.0f;
+        st[e] = RAW ? p[e] : 0.0f;
+        sh[e] = RAW ? r[e] : 0.0f;
+        acc[e] = RAW ? c0 * (p[e] - r[e]) : 0.0f;
     }
     // Columns 1..m-1 in chunks of kApplyChunk, software-pipelined over a real
     // (not unrolled) loop: the loads of the next chunk are issued before the
     // current chunk is consumed, so 2*kApplyChunk 128-bit loads per lane stay in
     // flight while the register footprint stays bounded.
-    float th[kApplyChunk][R], gr[kApplyChunk][R];
+    using Raw = typename RawRows<DT, R>::type;
+    Raw th[kApplyChunk] = {}, gr[kApplyChunk] = {};
 #pragma unroll
     for (int u = 0; u < kApplyChunk; ++u)
         if (1 + u < m) {
-            load_vec<DT, R>(thetas, (1 + u) * ld + row, th[u]);
-            load_vec<DT, R>(grads, (1 + u) * ld + row, gr[u]);
+            th[u] = load_raw<DT, R>(thetas, (1 + u) * ld + row);
+            gr[u] = load_raw<DT, R>(grads, (1 + u) * ld + row);
         }
 #pragma unroll 1
     for (int k0 = 1; k0 < m; k0 += kApplyChunk) {
-        float thn[kApplyChunk][R], grn[kApplyChunk][R];
+        Raw thn[kApplyChunk] = {}, grn[kApplyChunk] = {};
         const int kn = k0 + kApplyChunk;
 #pragma unroll
         for (int u = 0; u < kApplyChunk; ++u)
             if (kn + u < m) {
-                load_vec<DT, R>(thetas, (kn + u) * ld + row, thn[u]);
-                load_vec<DT, R>(grads, (kn + u) * ld + row, grn[u]);
+                thn[u] = load_raw<DT, R>(thetas, (kn + u) * ld + row);
+                grn[u] = load_raw<DT, R>(grads, (kn + u) * ld + row);
             }
 #pragma unroll
         for (int u = 0; u < kApplyChunk; ++u)
             if (k0 + u < m) {
                 const float ck = c[k0 + u];
+                float tv[R], gv[R];
+                unpack_rows<DT, R>(th[u], tv);
+                unpack_rows<DT, R>(gr[u], gv);
 #pragma unroll
                 for (int e = 0; e < R; ++e) {
-                    const float t = th[u][e] - p[e];
-                    const float h = gr[u][e] - r[e];
+                    const float t = RAW ? tv[e] : tv[e] - p[e];
+                    const float h = RAW ? gv[e] : gv[e] - r[e];
                     st[e] += t;
                     sh[e] += h;
                     acc[e] = fmaf(ck, t - h, acc[e]);
                 }
             }
 #pragma unroll
-        for (int u = 0; u < kApplyChunk; ++u)
-#pragma unroll
-            for (int e = 0; e < R; ++e) {
-                th[u][e] = thn[u][e];
-                gr[u][e] = grn[u][e];
-            }
+        for (int u = 0; u < kApplyChunk; ++u) {
+            th[u] = thn[u];
+            gr[u] = grn[u];
+        }
     }
     float zz[R];
     if (z != nullptr) {   // uniform
@@ -153,7 +215,10 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
     for (int e = 0; e < R; ++e) {
         const float mt = st[e] * inv_m, mh = sh[e] * inv_m;
         const float corr = acc[e] - csum * (mt - mh);
-        res[e] = z != nullptr ? zz[e] + corr : (p[e] + mt) - tau * ((r[e] + mh) + corr);
+        if constexpr (RAW)      // mt, mh are theta_bar, g_bar themselves
+            res[e] = z != nullptr ? zz[e] + corr : mt - tau * (mh + corr);
+        else
+            res[e] = z != nullptr ? zz[e] + corr : (p[e] + mt) - tau * ((r[e] + mh) + corr);
     }
 }
 

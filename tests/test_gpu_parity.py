@@ -194,7 +194,10 @@ def test_apply_matches_oracle(name, n, m):
     # the correction alone (difference to the SGD form) is also right
     sgd = oracle.apply_closed_form(th_np, gr_np, np.zeros(m), wl.tau)
     if m > 1:
-        assert rel(out.cpu().numpy().astype(np.float64) - sgd, ref - sgd) <= 1e-4
+        # bf16 storage sums the stored values in fp32 (no pivot differences): the
+        # correction on its own is good to the storage type's 1e-3, not to 1e-4
+        tol = 1e-4 if wl.storage == "f32" else 1e-3
+        assert rel(out.cpu().numpy().astype(np.float64) - sgd, ref - sgd) <= tol
 
 
 def test_apply_shards_and_unaligned():
