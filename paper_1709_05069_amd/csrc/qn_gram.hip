@@ -120,31 +120,24 @@ __device__ __forceinline__ void lds_rows8(const char *p, float (&x)[8])
     }
 }
 
-// The shifted entry d = present ? (keep_raw ? x : x - s) : 0.
-__device__ __forceinline__ float shifted(float x, float s, bool present, bool keep_raw)
-{
-    return present ? (keep_raw ? x : x - s) : 0.0f;
-}
-
 // Upper halves of two fp32 words as a bf16 pair (truncation).
 __device__ __forceinline__ uint32_t upper_halves(uint32_t u0, uint32_t u1)
 {
     return __builtin_amdgcn_perm(u1, u0, 0x07060302u);
 }
 
-// d for 8 rows, split into bf16 hi + lo: hi = the upper 16 bits of d,
-// lo = bf16(d - hi).  Exact whenever d has at most 16 significant bits (always
-// for bf16 storage, unless x and s differ by more than 2^8 in magnitude), else
-// good to 2^-16.
+// The shifted entry d = x - s for 8 rows (s: the pivot's rows, or zeros in the
+// pivot lane, which keeps its own value), split into bf16 hi + lo: hi = the
+// upper 16 bits of d, lo = bf16(d - hi).  Exact whenever d has at most 16
+// significant bits (always for bf16 storage, unless x and s differ by more than
+// 2^8 in magnitude), else good to 2^-16.
 __device__ __forceinline__ void split_bf16(const float (&x)[8], const float (&s)[8],
-                                           bool present, bool keep_raw, v8bf &hi,
-                                           v8bf &lo)
+                                           v8bf &hi, v8bf &lo)
 {
     uint32_t hw[4], lw[4];
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-        const float d0 = shifted(x[2 * h], s[2 * h], present, keep_raw);
-        const float d1 = shifted(x[2 * h + 1], s[2 * h + 1], present, keep_raw);
+        const float d0 = x[2 * h] - s[2 * h], d1 = x[2 * h + 1] - s[2 * h + 1];
         const uint32_t u0 = __float_as_uint(d0), u1 = __float_as_uint(d1);
         hw[h] = upper_halves(u0, u1);
         const float l0 = d0 - __uint_as_float(u0 & 0xffff0000u);
@@ -161,14 +154,12 @@ __device__ __forceinline__ void split_bf16(const float (&x)[8], const float (&s)
 // truncation: hi = the leading 8 significant bits of d, mid = the leading 8 of
 // d - hi, lo = the rest (at most 8 bits, so its upper half is all of it).
 __device__ __forceinline__ void split3_bf16(const float (&x)[8], const float (&s)[8],
-                                            bool present, bool keep_raw, v8bf &hi,
-                                            v8bf &mid, v8bf &lo)
+                                            v8bf &hi, v8bf &mid, v8bf &lo)
 {
     uint32_t hw[4], mw[4], lw[4];
 #pragma unroll
     for (int h = 0; h < 4; ++h) {
-        const float d0 = shifted(x[2 * h], s[2 * h], present, keep_raw);
-        const float d1 = shifted(x[2 * h + 1], s[2 * h + 1], present, keep_raw);
+        const float d0 = x[2 * h] - s[2 * h], d1 = x[2 * h + 1] - s[2 * h + 1];
         const uint32_t u0 = __float_as_uint(d0), u1 = __float_as_uint(d1);
         hw[h] = upper_halves(u0, u1);
         const float r0 = d0 - __uint_as_float(u0 & 0xffff0000u);
@@ -225,10 +216,14 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     const int group = lane >> 4;
     const int sub = col / MP;                            // this lane's row block (0 when PACK = 1)
     const bool is_pivot = col % MP == 0;
-    bool has[NT];
+    // LDS slot of this lane's column in set t.  A lane whose column does not exist
+    // (>= m) reads the pivot's slot instead: its shifted entry s - s is an exact
+    // zero, so no per-element select is needed.
+    const int pivot_slot = sub * MP;
+    int my_slot[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
-        has[t] = col % MP + 16 * t < m;
+        my_slot[t] = (col % MP + 16 * t < m) ? col + 16 * t : pivot_slot;
     const char *base = static_cast<const char *>(grads);
 
     const int64_t num_tiles = (n + TROWS - 1) / TROWS;
@@ -350,10 +345,10 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
             for (int sl = 0; sl < SLICES; ++sl) {
                 const char *at = stage + byte0 + sl * 8 * LESZ;
                 float x[NT][8], s[8];
-                lds_rows8<FMT>(at + sub * MP * kColPitch, s);    // the pivot: column 0 of this row block
+                lds_rows8<FMT>(at + pivot_slot * kColPitch, s);  // the pivot: column 0 of this row block
 #pragma unroll
                 for (int t = 0; t < NT; ++t)
-                    lds_rows8<FMT>(at + (col + 16 * t) * kColPitch, x[t]);
+                    lds_rows8<FMT>(at + my_slot[t] * kColPitch, x[t]);
                 [[maybe_unused]] v8bf zlo = {};                  // z's third term (bf16 storage)
                 if constexpr (HAS_Z) {
                     // the same 8 rows of z; only the pivot lane uses them
@@ -365,6 +360,12 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
                             x[0][e] = zr[e];
                     }
                 }
+                // column 0 itself is not shifted: in set 0 the pivot lane keeps its
+                // own value (or z) by subtracting zeros
+                float s0[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    s0[e] = is_pivot ? 0.0f : s[e];
                 if constexpr (DT == QN_F32) {
                     // d = hi + mid + lo exactly (8 + 8 + 8 bits); the six products
                     // down to 2^-16 of the leading one are kept, the dropped ones
@@ -372,7 +373,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
                     v8bf hi[NT], mid[NT], lo[NT];
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
-                        split3_bf16(x[t], s, has[t], t == 0 && is_pivot, hi[t], mid[t], lo[t]);
+                        split3_bf16(x[t], t == 0 ? s0 : s, hi[t], mid[t], lo[t]);
 #pragma unroll
                     for (int ti = 0; ti < NT; ++ti)
 #pragma unroll
@@ -390,13 +391,13 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
                     v8bf hi[NT], lo[NT];
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
-                        split_bf16(x[t], s, has[t], t == 0 && is_pivot, hi[t], lo[t]);
+                        split_bf16(x[t], t == 0 ? s0 : s, hi[t], lo[t]);
                     if constexpr (HAS_Z) {
                         // z is an arbitrary fp32 vector: its lane gets the exact
                         // three-term split, the third term through one more product
                         // per tile of column set 0
                         v8bf zh, zm, zl3;
-                        split3_bf16(x[0], s, true, true, zh, zm, zl3);
+                        split3_bf16(x[0], s0, zh, zm, zl3);
                         if (is_pivot) {
                             hi[0] = zh;
                             lo[0] = zm;
