@@ -291,6 +291,9 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
 template <int DT> struct StagedThreads {
     static constexpr int value = DT == QN_F32 ? QN_STAGED_THREADS_F32 : QN_STAGED_THREADS_BF16;
 };
+#ifndef QN_STAGED_BLOCKS_PER_CU
+#define QN_STAGED_BLOCKS_PER_CU 1
+#endif
 #ifndef QN_STAGED_LDS_KB
 #define QN_STAGED_LDS_KB 128
 #endif
@@ -430,7 +433,7 @@ int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
     const int64_t slab_rows = kStagedLdsBytes / 4;
     if (vec && n >= slab_rows * cu_count) {
         shape = ApplyShape::kStaged;
-        grid = cu_count;
+        grid = cu_count * QN_STAGED_BLOCKS_PER_CU;
     }
 
     TraceScope ts(QN_K_APPLY, stream);
