@@ -96,7 +96,8 @@ int qn_shutdown(void);
  * lambda        : cutoff of the rule after eq. (3)
  * theta_new     : n fp32 values (device, written)
  * j_out         : one int (device, written): the selected j, or 0 / -1 as above
- * Four kernels groups run back to back on `stream` with no host round trip. */
+ * Four kernels run back to back on `stream` (Gram pass, its reduction, the
+ * eigen kernel, the apply pass) with no host round trip. */
 int qn_update(const float *thetas, const float *grads, int64_t n, int m,
               float tau, float lambda, float *theta_new, int *j_out,
               qn_stream_t stream);
