@@ -55,6 +55,11 @@
  *   Because the all-ones vector is an exact null vector of G^T G whose computed
  *   singular value is of order 1e-8*sigma_1, lambda below about 1e-6 cannot
  *   separate it and is outside the supported range.
+ *   The Gram pass accumulates products of centred gradient entries in fp32 (fp64
+ *   from one tile on): entries of G whose squares leave the fp32 range are outside
+ *   the domain.  Below about 1e-19 in magnitude they underflow and the step
+ *   degrades to j_out = 0 (averaged SGD); above about 1e19 they overflow and the
+ *   step reports j_out = -1.  Scale the gradients (and tau) if they live there.
  */
 #ifndef QN_H
 #define QN_H

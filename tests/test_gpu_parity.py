@@ -308,3 +308,73 @@ def test_cutoff_below_full_rank_on_engineered_workers():
                               torch.tensor(grads, device=DEV), tau, lam)
         assert int(j.item()) == ref["j"]
         assert rel(out.cpu().numpy(), ref["theta_new"]) <= 1e-5
+
+
+# ------------------------------------------------ harder inputs, fused path ----
+def _engineered_states(n, m, svals, seed, g_offset=0.0, g_scale=1.0):
+    """Worker states whose centred gradient matrix has the given singular values
+    (times g_scale), on top of a common gradient g_offset + N(0,1)."""
+    rng = np.random.default_rng(seed)
+    U, _ = np.linalg.qr(rng.standard_normal((n, m - 1)))
+    M = rng.standard_normal((m, m))
+    M[:, 0] = 1.0
+    W = np.linalg.qr(M)[0][:, 1:]
+    G = (U * np.asarray(svals)) @ W.T
+    grads = ((G + rng.standard_normal(n)[:, None] + g_offset) * g_scale).T.astype(np.float32)
+    thetas = (rng.standard_normal(n)[None, :] + 0.05 * rng.standard_normal((m, n))).astype(np.float32)
+    return np.ascontiguousarray(thetas), np.ascontiguousarray(grads)
+
+
+@pytest.mark.parametrize("m,lam,expect_j", [(32, 0.5, 6), (32, 0.1, 18), (32, 0.03, 27),
+                                            (64, 0.25, 22), (12, 0.3, 4)])
+def test_update_cutoff_inside_the_fused_step(m, lam, expect_j):
+    # geometric spectrum: the cutoff falls strictly inside it, so the fused step
+    # (raw accumulators -> eigen kernel -> apply) has to drop directions
+    n = 40_000
+    svals = 3.0 * np.geomspace(1.0, 0.02, m - 1)
+    thetas, grads = _engineered_states(n, m, svals, 100 + m)
+    ref = oracle_full(thetas, grads, 0.8, np.float32(lam))
+    assert ref["j"] == expect_j
+    margin = np.min(np.abs(ref["sigma"][:m - 1] / ref["sigma"][0] - np.float32(lam)))
+    assert margin > 1e-4
+    th, gr = torch.tensor(thetas, device=DEV), torch.tensor(grads, device=DEV)
+    out, j = qn.qn_update(th, gr, 0.8, lam)
+    assert int(j.item()) == expect_j
+    assert rel(out.cpu().numpy(), ref["theta_new"]) <= 1e-5
+    # the step on its own; the coefficient along v_k carries ~1e-7 (sigma_1/sigma_k)^2
+    tb = oracle.row_means(thetas)
+    amp = (ref["sigma"][0] / ref["sigma"][expect_j - 1]) ** 2
+    assert rel(out.cpu().numpy().astype(np.float64) - tb, ref["theta_new"] - tb) <= 1e-6 * max(amp, 10.0)
+
+
+@pytest.mark.parametrize("g_offset,g_scale", [(1e3, 1.0), (0.0, 1e-12), (0.0, 1e12), (50.0, 1e-6)])
+def test_update_with_large_common_gradient_and_extreme_scales(g_offset, g_scale):
+    # a common gradient a million times the centred part (the raw Gram would lose
+    # everything; the pivot-shifted one must not), and gradient scales whose
+    # squares are still inside the fp32 range
+    n, m = 30_000, 16
+    svals = 1e-3 * np.geomspace(1.0, 0.2, m - 1) * np.sqrt(n)
+    thetas, grads = _engineered_states(n, m, svals, 7, g_offset, g_scale)
+    ref = oracle_full(thetas, grads, 1e-3 / g_scale, np.float32(0.05))
+    assert ref["j"] == m - 1
+    th, gr = torch.tensor(thetas, device=DEV), torch.tensor(grads, device=DEV)
+    C, w = qn.qn_gram(gr)
+    assert rel(C.cpu().numpy(), ref["C"]) <= 1e-5 and rel(w.cpu().numpy(), ref["w"]) <= 1e-5
+    out, j = qn.qn_update(th, gr, 1e-3 / g_scale, 0.05)
+    assert int(j.item()) == m - 1
+    assert rel(out.cpu().numpy(), ref["theta_new"]) <= 1e-5
+
+
+def test_gradient_magnitudes_outside_the_fp32_range_of_their_squares():
+    # documented in qn.h: centred entries below ~1e-19 underflow in the Gram pass
+    # (j = 0: averaged SGD), above ~1e19 they overflow (j = -1: c = 0, the SGD form)
+    n, m = 20_000, 8
+    svals = np.geomspace(1.0, 0.3, m - 1) * np.sqrt(n)
+    for scale, want_j in ((1e-25, 0), (1e25, -1)):
+        thetas, grads = _engineered_states(n, m, svals, 3, 0.0, scale)
+        th, gr = torch.tensor(thetas, device=DEV), torch.tensor(grads, device=DEV)
+        tau = 1e-3 / scale
+        out, j = qn.qn_update(th, gr, tau, 0.05)
+        assert int(j.item()) == want_j
+        sgd = oracle.apply_closed_form(thetas, grads, np.zeros(m), np.float32(tau))
+        assert rel(out.cpu().numpy(), sgd) <= 2e-6
