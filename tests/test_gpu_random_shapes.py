@@ -1,0 +1,79 @@
+"""Seeded random shapes: m, n, storage type, leading dimension and base-pointer
+offset drawn at random (ragged tiles, every alignment, row shards of a wider
+matrix), each compared with the oracle: Gram, whole step and the operator on a
+random vector."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1709_05069_amd as qn
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+M_CHOICES = [1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 24, 31, 32, 33, 40, 48, 49, 63, 64]
+N_EDGES = [255, 256, 257, 511, 513, 1023, 1025, 2047, 2049, 4095, 4097, 8193]
+
+
+def rel(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    nb = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / (nb if nb > 0 else 1.0)
+
+
+def stored(t):
+    t = t.contiguous()
+    return t.view(torch.uint16).cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_match_the_oracle(seed):
+    rng = np.random.default_rng(1000 + seed)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    for case in range(12):
+        m = int(rng.choice(M_CHOICES))
+        # n well above m: with n ~ m the step is ill conditioned (see the operator tests)
+        n = int(rng.choice(N_EDGES)) if rng.random() < 0.4 else int(rng.integers(100 * m, 100 * m + 30_000))
+        n = max(n, 100 * m)
+        bf = rng.random() < 0.4
+        ld = n + int(rng.integers(0, 9))
+        off = int(rng.integers(0, 8))
+        lam = float(rng.choice([0.01, 0.05, 0.3]))
+        tau = float(rng.choice([1.0, 0.5]))
+        tag = f"seed={seed} case={case} m={m} n={n} bf16={bf} ld={ld} offset={off} lam={lam}"
+        print(tag, flush=True)
+        dt = torch.bfloat16 if bf else torch.float32
+        buf_t = torch.empty(m * ld + off + 8, dtype=dt, device=DEV)
+        buf_g = torch.empty_like(buf_t)
+        th = buf_t[off:off + m * ld].view(m, ld)[:, :n]
+        gr = buf_g[off:off + m * ld].view(m, ld)[:, :n]
+        rnd = lambda *shape: torch.randn(*shape, device=DEV, generator=gen)
+        a = torch.exp(1.5 * rnd(n))
+        b = rnd(n)
+        th.copy_((rnd(n)[None, :] + 0.01 * rnd(m, n)).to(dt))
+        gr.copy_((a[None, :] * th.float() - b[None, :] + 0.01 * rnd(m, n)).to(dt))
+        th_np, gr_np = stored(th), stored(gr)
+
+        C, w = qn.qn_gram(gr)
+        Co, wo = oracle.gram_accumulate(gr_np)
+        if m > 1:
+            assert rel(C.cpu().numpy(), Co) <= 1e-5 and rel(w.cpu().numpy(), wo) <= 1e-5, tag
+        else:
+            assert torch.all(C == 0) and torch.all(w == 0), tag
+        ref = oracle.update_streaming(th_np, gr_np, tau, np.float32(lam))
+        sig = ref["sigma"]
+        margin = np.min(np.abs(sig[:max(m - 1, 1)] / sig[0] - np.float32(lam))) if sig[0] > 0 else 1.0
+        out, j = qn.qn_update(th, gr, tau, lam)
+        z = rnd(n)
+        h, jh = qn.qn_hinv(th, gr, z, lam)
+        if margin > 1e-5:                     # else "same j" is not well posed
+            assert int(j.item()) == ref["j"] and int(jh.item()) == ref["j"], tag
+            tol = 1e-3 if bf else 1e-5
+            assert rel(out.cpu().numpy(), ref["theta_new"]) <= tol, tag
+            tb, gb = oracle.row_means(th_np), oracle.row_means(gr_np)
+            href = oracle.apply_Hinv_literal(oracle.centre(th_np, tb), oracle.centre(gr_np, gb),
+                                             ref["sigma"], ref["V"], ref["j"],
+                                             z.cpu().numpy().astype(np.float64))
+            assert rel(h.cpu().numpy(), href) <= max(tol, 1e-4), tag
