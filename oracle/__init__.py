@@ -19,7 +19,7 @@ from . import build as _build
 
 _LIB = None
 
-F32, BF16, F64 = 0, 1, 2
+F32, BF16, F64, F16 = 0, 1, 2, 3
 
 _i64 = ctypes.c_int64
 _int = ctypes.c_int
@@ -84,7 +84,9 @@ def _code(a: np.ndarray) -> int:
     if a.dtype == np.float64:
         return F64
     if a.dtype == np.uint16:
-        return BF16
+        return BF16          # bfloat16 bit patterns (numpy has no such type)
+    if a.dtype == np.float16:
+        return F16
     raise TypeError(f"unsupported worker-matrix dtype {a.dtype}")
 
 

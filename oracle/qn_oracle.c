@@ -25,6 +25,19 @@ static double elem(const void *base, int dtype, int64_t idx)
         memcpy(&f, &bits, sizeof f);
         return (double)f;
     }
+    if (dtype == QNO_F16) {
+        /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+        const uint16_t h = ((const uint16_t *)base)[idx];
+        const int sign = h >> 15, e = (h >> 10) & 0x1f, frac = h & 0x3ff;
+        double v;
+        if (e == 0)
+            v = ldexp((double)frac, -24);                  /* zero and subnormals */
+        else if (e == 31)
+            v = frac ? NAN : INFINITY;
+        else
+            v = ldexp((double)(frac | 0x400), e - 25);     /* (1 + frac/1024) 2^(e-15) */
+        return sign ? -v : v;
+    }
     return ((const double *)base)[idx];
 }
 

@@ -31,7 +31,7 @@
 extern "C" {
 #endif
 
-typedef enum { QNO_F32 = 0, QNO_BF16 = 1, QNO_F64 = 2 } qno_dtype;
+typedef enum { QNO_F32 = 0, QNO_BF16 = 1, QNO_F64 = 2, QNO_F16 = 3 } qno_dtype;
 
 /* Section 2, the display after eq. (1): mean over the m workers, per row.
  * mean[i] = (1/m) sum_k X[i,k].  mean has n entries. */

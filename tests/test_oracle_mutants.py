@@ -38,6 +38,9 @@ MUTANTS = [
     ("closed form correction sign", "theta_new[i] = tbar - tau * (gbar + corr);",
      "theta_new[i] = tbar - tau * (gbar - corr);"),
     ("bf16 shift", "<< 16;", "<< 15;"),
+    ("f16 exponent bias", "v = ldexp((double)(frac | 0x400), e - 25);",
+     "v = ldexp((double)(frac | 0x400), e - 24);"),
+    ("f16 subnormals dropped", "v = ldexp((double)frac, -24);", "v = 0.0;"),
     ("transposed eigenvector storage", "c[r] += Vl[k * m + r] * a / sg[k];",
      "c[r] += Vl[r * m + k] * a / sg[k];"),
     ("cap from the eigenvalue", "return cap_tau(tau, s2 > 0.0, sqrt(s2), sigma_max);",

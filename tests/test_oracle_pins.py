@@ -60,6 +60,19 @@ def test_bf16_widening_exact():
     assert got.tolist() == [1.0, -2.0, 1.5, 0.0, -0.25]
 
 
+def test_f16_widening_every_bit_pattern():
+    # all 65536 IEEE binary16 patterns against numpy's own conversion (hand values
+    # first: 1, -2, the smallest subnormal 2^-24, the largest finite 65504)
+    hand = np.array([[0x3C00, 0xC000, 0x0001, 0x7BFF]], np.uint16).view(np.float16)
+    assert oracle.row_means(hand).tolist() == [1.0, -2.0, 2.0 ** -24, 65504.0]
+    bits = np.arange(65536, dtype=np.uint16)[None, :]
+    got = oracle.row_means(bits.view(np.float16))      # m = 1: the mean is the value
+    want = bits.view(np.float16).astype(np.float64)[0]
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])          # (the mean of one value: -0 reads as +0)
+
+
 def test_means_and_centre_hand_values():
     # catches: mean over parameters instead of over workers, wrong divisor
     X = np.array([[1.0, 2.0, 3.0], [3.0, 6.0, 9.0], [5.0, 1.0, 0.0]])
