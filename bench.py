@@ -65,6 +65,8 @@ def main():
     ap.add_argument("--workload", default="gpt2_small")
     ap.add_argument("--n", type=int, default=0, help="override the row count")
     ap.add_argument("--m", type=int, default=0, help="override the worker count")
+    ap.add_argument("--storage", default="", choices=["", "f32", "bf16", "f16"],
+                    help="override the storage type of the workload")
     ap.add_argument("--no-read-probe", action="store_true",
                     help="skip the plain read-stream probe (8 GiB) that gives "
                          "the practical HBM read ceiling of this device")
@@ -93,6 +95,9 @@ def main():
     if args.m:
         from dataclasses import replace
         wl = replace(wl, m=args.m, name=f"{wl.name}@m={args.m}")
+    if args.storage:
+        from dataclasses import replace
+        wl = replace(wl, storage=args.storage, name=f"{wl.name}@{args.storage}")
     esz = 4 if wl.storage == "f32" else 2
 
     t0 = time.perf_counter()

@@ -22,8 +22,9 @@
  *   inputs, writes the outputs, and owns nothing the caller passes in.
  * Layout: a worker matrix is m contiguous columns; worker k's vector starts at
  *   element k*ld (ld >= n; the plain entry points use ld = n).  Element type
- *   is fp32, or bfloat16 for the *_bf16 entry points (accumulation is fp32 /
- *   fp64 either way, theta_new is always fp32).  Small matrices are stored
+ *   is fp32, or bfloat16 for the *_bf16 entry points; the *_ex entry points also
+ *   take IEEE binary16 (QN_F16).  Accumulation is fp32 / fp64 in every case and
+ *   theta_new is always fp32.  Small matrices are stored
  *   the same way: V[k*m + r] is component r of v_k.
  * Alignment: any element-aligned pointer and any n work.  Fastest when the
  *   base pointers are 16-byte aligned and ld*sizeof(elem) is a multiple of 16
@@ -81,7 +82,7 @@ typedef enum {
     QN_EARCH = -4     /* the current device is not gfx950 */
 } qn_status;
 
-typedef enum { QN_F32 = 0, QN_BF16 = 1 } qn_dtype;
+typedef enum { QN_F32 = 0, QN_BF16 = 1, QN_F16 = 2 } qn_dtype;
 
 typedef void *qn_stream_t; /* a hipStream_t */
 

@@ -92,7 +92,7 @@ TraceScope::~TraceScope()
 // --------------------------------------------------------------- validation --
 static bool bad_common(const void *a, int dtype, int64_t n, int m, int64_t ld)
 {
-    return a == nullptr || (dtype != QN_F32 && dtype != QN_BF16) || n < 1 ||
+    return a == nullptr || (dtype != QN_F32 && dtype != QN_BF16 && dtype != QN_F16) || n < 1 ||
            m < 1 || m > QN_MAX_M || ld < n;
 }
 

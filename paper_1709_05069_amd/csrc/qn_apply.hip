@@ -50,44 +50,21 @@ template <int DT> struct ApplyChunk {
     static constexpr int value = DT == QN_F32 ? QN_APPLY_CHUNK_F32 : QN_APPLY_CHUNK_BF16;
 };
 
-template <int DT, int R>
-__device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (&x)[R])
-{
-    if constexpr (DT == QN_F32) {
-        const float *p = static_cast<const float *>(base) + elem;
-        if constexpr (R == 4) {
-            const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f_elem *>(p));
-            x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
-        } else {
-            static_assert(R == 1, "fp32 rows per lane");
-            x[0] = *p;
-        }
-    } else {
-        const uint16_t *p = static_cast<const uint16_t *>(base) + elem;
-        if constexpr (R == 8) {
-            const v4u v = __builtin_nontemporal_load(reinterpret_cast<const v4u_elem *>(p));
-            const uint32_t u[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                x[2 * h + 0] = __uint_as_float(u[h] << 16);
-                x[2 * h + 1] = __uint_as_float(u[h] & 0xffff0000u);
-            }
-        } else {
-            static_assert(R == 1, "bf16 rows per lane");
-            x[0] = __uint_as_float(static_cast<uint32_t>(*p) << 16);
-        }
-    }
-}
-
-// The same load kept as it arrives (16 bytes, or one element), and its unpacking
-// to fp32.  The pipelined loop below carries loads across iterations in this
-// form: unpacking bf16 at load time would make every iteration wait for the
-// loads it has just issued.
+// One load of R rows of a column kept as it arrives (16 bytes, or one element),
+// and its unpacking to fp32.  The pipelined loop below carries loads across
+// iterations in this form: unpacking 16-bit values at load time would make every
+// iteration wait for the loads it has just issued.
 template <int DT, int R> struct RawRows {
     using type = v4u;           // R == 4 fp32 values or R == 8 bf16 values
 };
 template <> struct RawRows<QN_F32, 1> { using type = float; };
 template <> struct RawRows<QN_BF16, 1> { using type = uint16_t; };
+template <> struct RawRows<QN_F16, 1> { using type = uint16_t; };
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+}
 
 template <int DT, int R>
 __device__ __forceinline__ typename RawRows<DT, R>::type load_raw(const void *base, int64_t elem)
@@ -109,22 +86,36 @@ __device__ __forceinline__ void unpack_rows(const typename RawRows<DT, R>::type 
     if constexpr (R == 1) {
         if constexpr (DT == QN_F32)
             x[0] = v;
-        else
+        else if constexpr (DT == QN_BF16)
             x[0] = __uint_as_float(static_cast<uint32_t>(v) << 16);
+        else
+            x[0] = half_bits_to_float(v);
     } else {
         const uint32_t u[4] = {v.x, v.y, v.z, v.w};
         if constexpr (DT == QN_F32) {
 #pragma unroll
             for (int e = 0; e < 4; ++e)
                 x[e] = __uint_as_float(u[e]);
-        } else {
+        } else if constexpr (DT == QN_BF16) {
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 x[2 * h + 0] = __uint_as_float(u[h] << 16);
                 x[2 * h + 1] = __uint_as_float(u[h] & 0xffff0000u);
             }
+        } else {
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                x[2 * h + 0] = half_bits_to_float(u[h] & 0xffffu);
+                x[2 * h + 1] = half_bits_to_float(u[h] >> 16);
+            }
         }
     }
+}
+
+template <int DT, int R>
+__device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (&x)[R])
+{
+    unpack_rows<DT, R>(load_raw<DT, R>(base, elem), x);
 }
 
 // theta_new for rows [row, row + R), from every worker column.
@@ -138,12 +129,12 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
                                              float (&res)[R])
 {
     constexpr int kApplyChunk = ApplyChunk<DT>::value;
-    // bf16 storage: the inputs carry 8 significant bits, so plain fp32 sums of the
+    // 16-bit storage: the inputs carry 8 or 11 significant bits, so plain fp32 sums of the
     // stored values (St = sum theta_k, acc = sum c_k (theta_k - g_k), error about
     // 1e-7 of the values) are far inside the data's own resolution and save a
     // third of the arithmetic, which this path is short of (twice the elements
     // per byte).  fp32 storage keeps the pivot form.
-    constexpr bool RAW = DT == QN_BF16 && QN_APPLY_BF16_RAW;
+    constexpr bool RAW = DT != QN_F32 && QN_APPLY_BF16_RAW;
     const int m = MC ? MC : m_rt;
     float p[R], r[R], st[R], sh[R], acc[R];
     load_vec<DT, R>(thetas, row, p);
@@ -410,6 +401,8 @@ int setup_apply_kernels()
     QN_OPT_IN(QN_F32, 16); QN_OPT_IN(QN_F32, 32); QN_OPT_IN(QN_F32, 64);
     QN_OPT_IN(QN_BF16, 0); QN_OPT_IN(QN_BF16, 4); QN_OPT_IN(QN_BF16, 8);
     QN_OPT_IN(QN_BF16, 16); QN_OPT_IN(QN_BF16, 32); QN_OPT_IN(QN_BF16, 64);
+    QN_OPT_IN(QN_F16, 0); QN_OPT_IN(QN_F16, 4); QN_OPT_IN(QN_F16, 8);
+    QN_OPT_IN(QN_F16, 16); QN_OPT_IN(QN_F16, 32); QN_OPT_IN(QN_F16, 64);
 #undef QN_OPT_IN
     return ok ? QN_OK : QN_ELAUNCH;
 }
@@ -439,8 +432,10 @@ int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
     TraceScope ts(QN_K_APPLY, stream);
     if (dtype == QN_F32)
         launch_dt<QN_F32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, theta_new, stream);
-    else
+    else if (dtype == QN_BF16)
         launch_dt<QN_BF16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, theta_new, stream);
+    else
+        launch_dt<QN_F16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, theta_new, stream);
     return check_launch();
 }
 

@@ -96,7 +96,7 @@ int qn_update_bounded_ex(const void *thetas, const void *grads, int dtype, int64
                          float *theta_new, int *j_out, float *tau_out,
                          qn_stream_t stream)
 {
-    if (!thetas || !grads || (dtype != QN_F32 && dtype != QN_BF16) || n < 1 || m < 1 ||
+    if (!thetas || !grads || (dtype != QN_F32 && dtype != QN_BF16 && dtype != QN_F16) || n < 1 || m < 1 ||
         m > QN_MAX_M || ld < n || !theta_new || !j_out || !std::isfinite(tau) ||
         !std::isfinite(lambda) || !(lambda > 0.0f) ||
         (mode != QN_BOUND_SIGMA1 && mode != QN_BOUND_SECANT))

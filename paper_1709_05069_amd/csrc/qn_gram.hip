@@ -78,25 +78,44 @@ template <int DT, bool ALIGNED> struct StreamRows {
     static constexpr int value = (DT == QN_F32 || !ALIGNED) ? 256 : 512;
 };
 
-// 16 bytes of one column from LDS as fp32 row values.  FMT 0: fp32; 1: packed
-// bf16 (8 rows); 2: bf16 zero-extended to one dword per row (4 rows).
-template <int FMT>
-__device__ __forceinline__ void lds_rows(const char *p, float (&x)[FMT == 1 ? 8 : 4])
+// 16 bytes of one column from LDS as fp32 row values.  FMT 0: fp32 (4 rows);
+// 1: packed bf16 (8 rows); 2: bf16 zero-extended to one dword per row (4 rows);
+// 3: packed fp16 (8 rows); 4: fp16 zero-extended to one dword per row (4 rows).
+constexpr bool fmt_packed(int fmt) { return fmt == 1 || fmt == 3; }
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h)
 {
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+}
+
+template <int FMT>
+__device__ __forceinline__ void lds_rows(const char *p, float (&x)[fmt_packed(FMT) ? 8 : 4])
+{
+    const v4u v = *reinterpret_cast<const v4u *>(p);
+    const uint32_t u[4] = {v.x, v.y, v.z, v.w};
     if constexpr (FMT == 0) {
-        const v4f v = *reinterpret_cast<const v4f *>(p);
-        x[0] = v.x; x[1] = v.y; x[2] = v.z; x[3] = v.w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            x[e] = __uint_as_float(u[e]);
     } else if constexpr (FMT == 2) {
-        const v4u v = *reinterpret_cast<const v4u *>(p);
-        x[0] = __uint_as_float(v.x << 16); x[1] = __uint_as_float(v.y << 16);
-        x[2] = __uint_as_float(v.z << 16); x[3] = __uint_as_float(v.w << 16);
-    } else {
-        const v4u v = *reinterpret_cast<const v4u *>(p);
-        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            x[e] = __uint_as_float(u[e] << 16);
+    } else if constexpr (FMT == 4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            x[e] = half_bits_to_float(u[e]);
+    } else if constexpr (FMT == 1) {
 #pragma unroll
         for (int h = 0; h < 4; ++h) {
             x[2 * h + 0] = __uint_as_float(u[h] << 16);
             x[2 * h + 1] = __uint_as_float(u[h] & 0xffff0000u);
+        }
+    } else {
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            x[2 * h + 0] = half_bits_to_float(u[h] & 0xffffu);
+            x[2 * h + 1] = half_bits_to_float(u[h] >> 16);
         }
     }
 }
@@ -106,8 +125,8 @@ __device__ __forceinline__ void lds_rows(const char *p, float (&x)[FMT == 1 ? 8 
 template <int FMT>
 __device__ __forceinline__ void lds_rows8(const char *p, float (&x)[8])
 {
-    if constexpr (FMT == 1) {
-        lds_rows<1>(p, x);
+    if constexpr (fmt_packed(FMT)) {
+        lds_rows<FMT>(p, x);
     } else {
         float a[4], b[4];
         lds_rows<FMT>(p, a);
@@ -199,9 +218,9 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     constexpr int TROWS = ROWS * PACK;                   // rows per tile
     constexpr int MP = 16 / PACK;                        // column lanes per row block
     constexpr int ESZ = (DT == QN_F32) ? 4 : 2;          // element size in memory
-    constexpr bool WIDE = DT == QN_BF16 && !ALIGNED;     // bf16 kept one per dword in LDS
+    constexpr bool WIDE = DT != QN_F32 && !ALIGNED;      // 16-bit values kept one per dword in LDS
     constexpr int LESZ = WIDE ? 4 : ESZ;                 // element size in LDS
-    constexpr int FMT = DT == QN_F32 ? 0 : (WIDE ? 2 : 1);
+    constexpr int FMT = DT == QN_F32 ? 0 : (DT == QN_BF16 ? (WIDE ? 2 : 1) : (WIDE ? 4 : 3));
     constexpr int RPV = 16 / LESZ;                       // rows per 16-byte LDS vector
     constexpr int SLOTS_PER_WAVE = 16 * NT / kGramWaves; // column slots a wave loads
     constexpr int SLICES = ROWS / kGramWaves / 4 / 8;    // 8-row slices per lane group and tile
@@ -366,7 +385,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     s0[e] = is_pivot ? 0.0f : s[e];
-                if constexpr (DT == QN_F32) {
+                if constexpr (DT != QN_BF16) {
                     // d = hi + mid + lo exactly (8 + 8 + 8 bits); the six products
                     // down to 2^-16 of the leading one are kept, the dropped ones
                     // (mid lo, lo mid, lo lo) are below 2^-23 of it
@@ -589,7 +608,7 @@ static bool opt_in_dt()
 
 int setup_gram_kernels()
 {
-    return opt_in_dt<QN_F32>() && opt_in_dt<QN_BF16>() ? QN_OK : QN_ELAUNCH;
+    return opt_in_dt<QN_F32>() && opt_in_dt<QN_BF16>() && opt_in_dt<QN_F16>() ? QN_OK : QN_ELAUNCH;
 }
 
 int launch_gram_raw(const void *grads, int dtype, int64_t n, int m, int64_t ld,
@@ -611,9 +630,12 @@ int launch_gram_raw(const void *grads, int dtype, int64_t n, int m, int64_t ld,
         if (dtype == QN_F32) {
             if (aligned) { if (z) QN_GO(QN_F32, true, true); else QN_GO(QN_F32, true, false); }
             else { if (z) QN_GO(QN_F32, false, true); else QN_GO(QN_F32, false, false); }
-        } else {
+        } else if (dtype == QN_BF16) {
             if (aligned) { if (z) QN_GO(QN_BF16, true, true); else QN_GO(QN_BF16, true, false); }
             else { if (z) QN_GO(QN_BF16, false, true); else QN_GO(QN_BF16, false, false); }
+        } else {
+            if (aligned) { if (z) QN_GO(QN_F16, true, true); else QN_GO(QN_F16, true, false); }
+            else { if (z) QN_GO(QN_F16, false, true); else QN_GO(QN_F16, false, false); }
         }
 #undef QN_GO
     }

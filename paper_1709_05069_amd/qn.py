@@ -1,7 +1,7 @@
 """Argument marshalling for libqn's C ABI: torch tensors in, torch tensors out.
 
 Worker matrices are (m, n) tensors whose rows are the workers' vectors
-(stride(1) == 1; stride(0) = ld >= n), dtype float32 or bfloat16, on the HIP
+(stride(1) == 1; stride(0) = ld >= n), dtype float32, bfloat16 or float16, on the HIP
 device.  Every step of the computation runs in the library's kernels; torch
 only owns the memory and the stream.
 """
@@ -11,7 +11,7 @@ import torch
 
 from . import _lib
 
-QN_F32, QN_BF16 = 0, 1
+QN_F32, QN_BF16, QN_F16 = 0, 1, 2
 KERNEL_NAMES = ("gram_stage1", "gram_reduce", "gram_project", "eig_select",
                 "apply_kernel", "coef", "tau_bound")
 
@@ -40,6 +40,8 @@ def _worker(t: torch.Tensor, name: str):
         dt = QN_F32
     elif t.dtype == torch.bfloat16:
         dt = QN_BF16
+    elif t.dtype == torch.float16:
+        dt = QN_F16
     else:
         raise QnError(f"{name}: unsupported dtype {t.dtype}")
     m, n = t.shape

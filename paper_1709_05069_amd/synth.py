@@ -31,7 +31,7 @@ class Workload:
     name: str
     n: int
     m: int
-    storage: str          # "f32" or "bf16"
+    storage: str          # "f32", "bf16" or "f16"
     a_lo: float
     a_hi: float
     blocks: int           # 0: per-element log-uniform curvature
@@ -61,7 +61,7 @@ WORKLOADS = {
 
 
 def torch_dtype(storage: str) -> torch.dtype:
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[storage]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[storage]
 
 
 def _block_scales(wl: Workload) -> torch.Tensor:

@@ -1,4 +1,4 @@
-"""Seeded random shapes: m, n, storage type, leading dimension and base-pointer
+"""Seeded random shapes: m, n, storage type (fp32, bf16, fp16), leading dimension and base-pointer
 offset drawn at random (ragged tiles, every alignment, row shards of a wider
 matrix), each compared with the oracle: Gram, whole step and the operator on a
 random vector."""
@@ -23,7 +23,7 @@ def rel(a, b):
 
 
 def stored(t):
-    t = t.contiguous()
+    t = t.contiguous()      # bf16 goes to the oracle as bit patterns, fp16 and fp32 as numpy's types
     return t.view(torch.uint16).cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
 
 
@@ -37,14 +37,15 @@ def test_random_shapes_match_the_oracle(seed):
         # n well above m: with n ~ m the step is ill conditioned (see the operator tests)
         n = int(rng.choice(N_EDGES)) if rng.random() < 0.4 else int(rng.integers(100 * m, 100 * m + 30_000))
         n = max(n, 100 * m)
-        bf = rng.random() < 0.4
+        kind = str(rng.choice(["f32", "f32", "bf16", "f16"]))
+        bf = kind != "f32"
         ld = n + int(rng.integers(0, 9))
         off = int(rng.integers(0, 8))
         lam = float(rng.choice([0.01, 0.05, 0.3]))
         tau = float(rng.choice([1.0, 0.5]))
-        tag = f"seed={seed} case={case} m={m} n={n} bf16={bf} ld={ld} offset={off} lam={lam}"
+        tag = f"seed={seed} case={case} m={m} n={n} storage={kind} ld={ld} offset={off} lam={lam}"
         print(tag, flush=True)
-        dt = torch.bfloat16 if bf else torch.float32
+        dt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[kind]
         buf_t = torch.empty(m * ld + off + 8, dtype=dt, device=DEV)
         buf_g = torch.empty_like(buf_t)
         th = buf_t[off:off + m * ld].view(m, ld)[:, :n]
