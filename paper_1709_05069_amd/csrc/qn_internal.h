@@ -11,7 +11,8 @@ namespace qn {
 
 // ---- fixed launch geometry -------------------------------------------------
 // The Gram pass runs a fixed grid so that the summation tree depends only on
-// (n, m, dtype).  Each block writes one partial; the partial holds the raw
+// (n, m, dtype, alignment) and the device's CU count.  Each block writes one
+// partial; the partial holds the raw
 // MFMA accumulator layout: kTileEntries values per 16x16 tile, 1, 3, 6 or 10
 // tiles (the lower triangle of a 1x1 .. 4x4 tiling: m <= 16, 32, 48, 64).
 #ifndef QN_GRAM_THREADS
