@@ -2,10 +2,12 @@
 include/qn.h declares, and its host-only entry points behave."""
 import os
 import re
+import subprocess
 
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "qn.h")
 
 
 def _declared_functions():
@@ -24,10 +26,20 @@ def lib():
     return _lib.load()
 
 
-def test_header_declares_the_north_star_entry_points():
+def test_header_declares_the_four_entry_points_of_the_step():
     names = _declared_functions()
     for required in ("qn_update", "qn_gram", "qn_eig", "qn_apply"):
         assert required in names
+
+
+def test_header_is_valid_c99(tmp_path):
+    # the boundary is a C ABI: the header must compile as plain C, not only as C++
+    src = tmp_path / "use_qn.c"
+    src.write_text('#include "qn.h"\nint main(void) { return QN_MAX_M > 0 ? 0 : 1; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror",
+                        "-fsyntax-only", "-I", os.path.dirname(HEADER), str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
 
 
 def test_every_declared_symbol_is_exported(lib):

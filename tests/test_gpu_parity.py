@@ -1,7 +1,7 @@
 """GPU parity: the HIP library (through its C ABI) against the CPU oracle,
 element by element on the same seeded inputs.
 
-Tolerances (stated by the task's headline metric and derived in the design doc):
+Tolerances:
   j                       exact
   theta_new               relative L2 <= 1e-5 (fp32 storage), <= 1e-3 (bf16 storage)
 internal, stricter than the headline needs:
