@@ -119,3 +119,34 @@ def test_fullsize_gpt2_small_headline():
 
 def test_fullsize_stress_1b_bf16():
     run_fullsize("stress_1b_bf16", 1 << 21, whole_vector=False)
+
+
+def test_more_than_two_to_the_31_rows():
+    # 64-bit row indexing: n > 2^31 with two workers (37 GB of inputs).  The oracle
+    # checks a sample of rows beyond 2^31; row shards check the rest through
+    # properties that hold at any size (the Gram matrix is additive over row
+    # shards, a shard's step equals the same rows of the whole step).
+    from dataclasses import replace
+    n, m = 2_300_000_001, 2
+    wl = replace(synth.WORKLOADS["gpt2_small"].scaled(n), m=m)
+    th, gr = synth.make_worker_states(wl, DEV)
+    C, w = qn.qn_gram(gr)
+    Cs, ws = torch.zeros_like(C), torch.zeros_like(w)
+    for r0 in range(0, n, 600_000_000):
+        c1, w1 = qn.qn_gram(gr[:, r0:r0 + 600_000_000])
+        Cs += c1
+        ws += w1
+    assert float((Cs - C).norm() / C.norm()) <= 1e-9 and float((ws - w).norm() / w.norm()) <= 1e-9
+    out, j = qn.qn_update(th, gr, wl.tau, wl.lam)
+    assert int(j.item()) == 1
+    _, _, c, _ = qn.qn_eig(C, w, wl.lam)
+    r0, rows = 2_200_000_003, 50_000_000
+    part = qn.qn_apply(th[:, r0:r0 + rows], gr[:, r0:r0 + rows], c, wl.tau)
+    assert float((part - out[r0:r0 + rows]).norm() / part.norm()) <= 1e-6
+    idx = slice(2_250_000_000, 2_250_200_000)
+    ref = oracle.apply_closed_form(th[:, idx].cpu().numpy(), gr[:, idx].cpu().numpy(),
+                                   c.cpu().numpy().astype(np.float64), wl.tau)
+    assert rel(out[idx].cpu().numpy(), ref) <= 1e-6
+    # and the coefficient vector itself against the oracle's, from the GPU's Gram
+    co = oracle.coefficients(C.cpu().numpy(), w.cpu().numpy(), np.float32(wl.lam))
+    assert co["j"] == 1 and rel(c.cpu().numpy(), co["c"]) <= 1e-6
