@@ -78,6 +78,17 @@ def test_argument_errors_are_reported_before_any_device_work(lib):
     assert lib.qn_update_ex(p, p, 0, 10, 4, 9, 1.0, 0.1, p, p, None) == -1   # ld < n
     assert lib.qn_update_ex(p, p, 7, 10, 4, 10, 1.0, 0.1, p, p, None) == -1  # dtype
     assert lib.qn_trace_end(None, None) == -1                            # not tracing
+    # the operator, its pieces and the capped step
+    assert lib.qn_hinv(p, p, None, 10, 4, 0.1, p, p, None) == -1         # z missing
+    assert lib.qn_hinv_ex(p, p, 0, p, 10, 4, 10, -1.0, p, p, None) == -1  # lambda <= 0
+    assert lib.qn_gemv_t_ex(p, 3, p, 10, 4, 10, p, None) == -1           # dtype
+    assert lib.qn_coef(p, p, p, p, 65, p, None) == -1                    # m > max
+    assert lib.qn_hinv_apply_ex(p, p, 0, p, 10, 4, 10, None, p, None) == -1   # c missing
+    assert lib.qn_update_bounded_ex(p, p, 0, 10, 4, 10, 1.0, 0.1, 0, p, p, p, None) == -1  # mode
+    assert lib.qn_update_bounded_ex(p, p, 0, 10, 4, 10, 1.0, 0.1, 3, p, p, p, None) == -1
+    assert lib.qn_tau_bound(p, p, p, None, 4, 1.0, 2, p, p, None) == -1  # secant needs Theta^T Theta
+    assert lib.qn_tau_bound(p, p, p, p, 4, float("nan"), 1, p, p, None) == -1
+    assert lib.qn_probe_copy(p, p, 24, None) == -1                       # not a multiple of 16
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

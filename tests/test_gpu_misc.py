@@ -94,6 +94,8 @@ def test_binding_rejects_bad_tensors():
         qn.qn_update(th, gr, 1.0, -0.5)                  # lambda <= 0: library says EINVAL
     with pytest.raises(qn.QnError):
         qn.qn_apply(th, gr, torch.zeros(3, device=DEV), 1.0)
+    with pytest.raises(qn.QnError):
+        qn.qn_update(th[:, :0], gr[:, :0], 1.0, 0.1)    # no rows
     big = torch.zeros((65, 64), device=DEV)
     with pytest.raises(qn.QnError):
         qn.qn_gram(big)                                  # m > QN_MAX_M
