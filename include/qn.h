@@ -35,11 +35,18 @@
  * Streams: all work is enqueued on `stream` (a hipStream_t passed as void*;
  *   NULL is the default stream) and the call returns without synchronising.
  *   j_out is written on the device; synchronise the stream before reading it.
- * Workspace: the first call on a device allocates a fixed workspace (about
- *   22 MB) with hipMalloc and keeps it until qn_shutdown(); later calls
- *   allocate nothing.  Calls on the same device share it: two calls that may
- *   overlap in time (different streams or host threads) race and must be
- *   serialised by the caller.
+ * Workspace: the Gram pass and the fused steps need scratch memory (block
+ *   partials, the reduced accumulators, the m x m intermediates): at most about
+ *   5.6 MB on a 256-unit device, qn_workspace_bytes() gives the figure for a
+ *   problem.  The *_ws entry points take it from the caller (device memory,
+ *   256-byte aligned, owned by the caller, contents undefined afterwards); they
+ *   allocate and free nothing, and calls with different workspaces may run
+ *   concurrently on different streams.  The entry points without a workspace
+ *   argument use one that the library allocates with hipMalloc on the first such
+ *   call on a device and keeps until qn_shutdown(); they share it, so two of
+ *   them that may overlap in time (different streams or host threads) race and
+ *   must be serialised by the caller.  qn_eig, qn_apply*, qn_coef,
+ *   qn_hinv_apply_ex and qn_tau_bound need no scratch memory.
  * Determinism: no floating-point atomics; the reduction tree is a function of
  *   (n, m, dtype, alignment) and the device's compute-unit count only, so
  *   results are bitwise reproducible run to run.
@@ -53,6 +60,20 @@
  *                 rows they occupy).
  * Domain: n >= 1, 1 <= m <= QN_MAX_M, tau finite, lambda > 0 and finite.  The
  *   paper takes 0 < lambda < 1; lambda > 1 is accepted and gives j = 0.
+ * Accuracy: with fp32 storage theta_new is within 1e-5 of the exact result of
+ *   eq. (2)-(4) on the stored inputs in relative L2 norm (1e-3 for 16-bit
+ *   storage) on well-conditioned steps.  What limits it is the Gram matrix: the
+ *   streaming pass (n > 16384) forms it to about eps_C = 1e-7 of its norm
+ *   (exact bf16-split products, fp32 sums over one tile, fp64 from there on;
+ *   problems of up to 16384 rows take an fp64 kernel and eps_C ~ 1e-15), and the
+ *   coefficient solve divides by sigma_k^2, so to first order
+ *       ||d theta_new|| <= tau * eps_C * (1 + max_{k<=j} ||Theta v_k||/sigma_k)
+ *                              * (sigma_1^2 ||c|| + ||w||) / sigma_j .
+ *   The factor sigma_1/sigma_j is at most 1/lambda.  The bound matters when
+ *   g_bar lies mostly inside span{u_1..u_j} (n of the order of m, or gradient
+ *   noise far below the curvature signal): then G c cancels g_bar and theta_new
+ *   can be much smaller than the terms it is made of.  The sums of the apply
+ *   pass run in fp64 for fp32 storage, so they add nothing to this.
  *   Because the all-ones vector is an exact null vector of G^T G whose computed
  *   singular value is of order 1e-8*sigma_1, lambda below about 1e-6 cannot
  *   separate it and is outside the supported range.
@@ -79,7 +100,9 @@ typedef enum {
     QN_EINVAL = -1,   /* bad argument (null pointer, n < 1, m out of range, bad scalar) */
     QN_ENOMEM = -2,   /* workspace allocation failed */
     QN_ELAUNCH = -3,  /* a HIP call or kernel launch reported an error */
-    QN_EARCH = -4     /* the current device is not gfx950 */
+    QN_EARCH = -4,    /* the current device is not gfx950 */
+    QN_EWORKSPACE = -5 /* workspace null, not 256-byte aligned or smaller than
+                          qn_workspace_bytes() for this problem */
 } qn_status;
 
 typedef enum { QN_F32 = 0, QN_BF16 = 1, QN_F16 = 2 } qn_dtype;
@@ -89,12 +112,20 @@ typedef void *qn_stream_t; /* a hipStream_t */
 /* host: static string for a status code */
 const char *qn_status_string(int status);
 
-/* Allocates the current device's workspace now instead of on first use.
- * Returns QN_OK, QN_ENOMEM, QN_EARCH or QN_ELAUNCH. */
+/* Prepares the current device (architecture check, kernel attributes) and
+ * allocates the library-owned workspace of the entry points that take none, now
+ * instead of on first use.  Returns QN_OK, QN_ENOMEM, QN_EARCH or QN_ELAUNCH. */
 int qn_init(void);
 
-/* Frees every device's workspace.  No library work may be in flight. */
+/* Frees every device's library-owned workspace.  No library work may be in flight. */
 int qn_shutdown(void);
+
+/* host: bytes of scratch memory a *_ws call on an n x m problem of this element
+ * type needs on the current device (any alignment of the inputs, any ld).  A
+ * pure function of its arguments and the device's compute-unit count (256 is
+ * assumed when no device can be queried); never more than about 5.6 MB.
+ * 0 for arguments outside the domain. */
+size_t qn_workspace_bytes(int64_t n, int m, int dtype);
 
 /* ---- the whole step: eq. (2) with the operator of eq. (3)/(4) -------------
  * thetas, grads : n x m worker matrices (device, read only)
@@ -157,6 +188,18 @@ int qn_apply_ex(const void *thetas, const void *grads, int dtype, int64_t n,
                 int m, int64_t ld, const float *c, float tau, float *theta_new,
                 qn_stream_t stream);
 
+/* ---- the same with caller-owned scratch memory --------------------------------
+ * workspace : device memory, 256-byte aligned, workspace_bytes >=
+ *   qn_workspace_bytes(n, m, dtype); otherwise QN_EWORKSPACE and nothing is
+ *   enqueued.  The library allocates nothing in these calls.  The workspace must
+ *   stay untouched until the work enqueued on `stream` has finished; the same
+ *   results, bit for bit, as the entry points above. */
+int qn_update_ws(const void *thetas, const void *grads, int dtype, int64_t n, int m,
+                 int64_t ld, float tau, float lambda, float *theta_new, int *j_out,
+                 void *workspace, size_t workspace_bytes, qn_stream_t stream);
+int qn_gram_ws(const void *grads, int dtype, int64_t n, int m, int64_t ld, double *C,
+               double *w, void *workspace, size_t workspace_bytes, qn_stream_t stream);
+
 /* ---- the operator of eq. (3)/(4) on an arbitrary vector ---------------------
  *   out = Hinv z = z_perp + sum_{k<=j} alpha_k sigma_k^-1 y_k,  alpha_k = z^T u_k,
  * identity on span{u_1..u_j}^perp and the secant inverse (G v_k -> Theta v_k) on
@@ -188,6 +231,13 @@ int qn_coef(const double *sigma, const double *V, const int *j, const double *w,
 int qn_hinv_apply_ex(const void *thetas, const void *grads, int dtype, const float *z,
                      int64_t n, int m, int64_t ld, const float *c, float *out,
                      qn_stream_t stream);
+/* with caller-owned scratch memory (see qn_update_ws) */
+int qn_hinv_ws(const void *thetas, const void *grads, int dtype, const float *z,
+               int64_t n, int m, int64_t ld, float lambda, float *out, int *j_out,
+               void *workspace, size_t workspace_bytes, qn_stream_t stream);
+int qn_gemv_t_ws(const void *grads, int dtype, const float *z, int64_t n, int m,
+                 int64_t ld, double *w, void *workspace, size_t workspace_bytes,
+                 qn_stream_t stream);
 
 /* ---- step size capped by 1 / sigma_max (Section 3, closing discussion) ------
  * The paper bounds tau above by the reciprocal of the largest singular value
@@ -215,41 +265,11 @@ int qn_update_bounded_ex(const void *thetas, const void *grads, int dtype, int64
 int qn_tau_bound(const double *sigma, const double *V, const int *j,
                  const double *C_theta, int m, float tau, int mode, float *tau_out,
                  double *sigma_max_out, qn_stream_t stream);
-
-/* ---- per-kernel timing (host side helper, for benchmarks) -----------------
- * Between qn_trace_begin() and qn_trace_end() every kernel the library
- * launches is bracketed by HIP events recorded on the launch stream.
- * qn_trace_end() synchronises those events and returns, per kernel id, the
- * summed duration in milliseconds and the launch count (host arrays of
- * QN_TRACE_KERNELS entries each), then disables tracing.
- * max_launches bounds the number of launches recorded (events are created in
- * qn_trace_begin, none in the timed region); further launches are not timed. */
-enum {
-    QN_K_GRAM = 0,     /* stage 1: streaming pass over grads, per-block partials */
-    QN_K_REDUCE = 1,   /* stage 2: fixed-order fp64 sum of the partials */
-    QN_K_PROJECT = 2,  /* m x m centring algebra producing C and w */
-    QN_K_EIG = 3,      /* Jacobi + cutoff + coefficients */
-    QN_K_APPLY = 4,    /* streaming pass over thetas and grads */
-    QN_K_COEF = 5,     /* coefficients from sigma, V, j, w */
-    QN_K_BOUND = 6,    /* capped step size from sigma, V, j (and Theta^T Theta) */
-    QN_TRACE_KERNELS = 7
-};
-int qn_trace_begin(int max_launches);
-int qn_trace_end(double *ms_sum /* host */, int *launches /* host */);
-/* host: static name of a kernel id */
-const char *qn_kernel_name(int kernel_id);
-
-/* ---- bandwidth probes (diagnostics; not part of the method) ----------------
- * Kernels of exactly known HBM traffic.  They calibrate hardware byte counters
- * and measure the streaming ceiling that the Gram and apply passes are compared
- * with.  bytes must be a positive multiple of 16, pointers 16-byte aligned.
- * qn_probe_copy : dst[0..bytes) = src[0..bytes); reads bytes, writes bytes.
- * qn_probe_read : reads src[0..bytes) and writes qn_probe_sink_floats() floats
- *                 of no meaning to sink (the caller sizes sink with that call;
- *                 it returns -1 when no gfx950 device is current). */
-int qn_probe_copy(const void *src, void *dst, int64_t bytes, qn_stream_t stream);
-int qn_probe_read(const void *src, int64_t bytes, float *sink, qn_stream_t stream);
-int qn_probe_sink_floats(void);
+/* with caller-owned scratch memory (see qn_update_ws) */
+int qn_update_bounded_ws(const void *thetas, const void *grads, int dtype, int64_t n,
+                         int m, int64_t ld, float tau, float lambda, int mode,
+                         float *theta_new, int *j_out, float *tau_out, void *workspace,
+                         size_t workspace_bytes, qn_stream_t stream);
 
 #ifdef __cplusplus
 }

@@ -10,8 +10,20 @@ _int = ctypes.c_int
 _f32 = ctypes.c_float
 _vp = ctypes.c_void_p
 
-# name -> (restype, argtypes); mirrors include/qn.h
+_sz = ctypes.c_size_t
+
+# name -> (restype, argtypes); mirrors include/qn.h and include/qn_diag.h
 SIGNATURES = {
+    "qn_workspace_bytes": (_sz, [_i64, _int, _int]),
+    "qn_update_ws": (_int, [_vp, _vp, _int, _i64, _int, _i64, _f32, _f32, _vp, _vp,
+                            _vp, _sz, _vp]),
+    "qn_gram_ws": (_int, [_vp, _int, _i64, _int, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "qn_hinv_ws": (_int, [_vp, _vp, _int, _vp, _i64, _int, _i64, _f32, _vp, _vp,
+                          _vp, _sz, _vp]),
+    "qn_gemv_t_ws": (_int, [_vp, _int, _vp, _i64, _int, _i64, _vp, _vp, _sz, _vp]),
+    "qn_update_bounded_ws": (_int, [_vp, _vp, _int, _i64, _int, _i64, _f32, _f32, _int,
+                                    _vp, _vp, _vp, _vp, _sz, _vp]),
+    "qn_diag_gram_ex": (_int, [_vp, _int, _vp, _i64, _int, _i64, _int, _vp, _vp, _vp]),
     "qn_status_string": (ctypes.c_char_p, [_int]),
     "qn_kernel_name": (ctypes.c_char_p, [_int]),
     "qn_init": (_int, []),

@@ -1,6 +1,7 @@
-// C ABI of libqn (declared in include/qn.h): argument validation, the
-// per-device workspace, the optional per-kernel event tracing, and the
-// composition of the kernels into the server step of Section 2, eq. (2)-(4).
+// C ABI of libqn (declared in include/qn.h and include/qn_diag.h): argument
+// validation, per-device set-up, workspaces, the optional per-kernel event
+// tracing, and the composition of the kernels into the server step of Section 2,
+// eq. (2)-(4).
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -10,21 +11,19 @@
 
 namespace qn {
 
-// ---------------------------------------------------------------- workspace --
+// ------------------------------------------------------------- device state --
 constexpr int kMaxDevices = 64;
-static Workspace g_ws[kMaxDevices];
-static bool g_ws_ready[kMaxDevices];
-static std::mutex g_ws_mutex;
+static Device g_dev[kMaxDevices];
+static bool g_dev_ready[kMaxDevices];
+static std::mutex g_dev_mutex;
 
-static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-int get_workspace(Workspace **out)
+int get_device(Device **out)
 {
     int dev = -1;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
         return QN_ELAUNCH;
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
-    if (!g_ws_ready[dev]) {
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (!g_dev_ready[dev]) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return QN_ELAUNCH;
@@ -33,36 +32,90 @@ int get_workspace(Workspace **out)
         if (setup_gram_kernels() != QN_OK || setup_apply_kernels() != QN_OK ||
             setup_eig_kernels() != QN_OK)
             return QN_ELAUNCH;
-        Workspace ws{};
-        ws.cu_count = prop.multiProcessorCount;
-        const size_t b_part = align_up(sizeof(double) * kGramMaxBlocks * kMaxEntries, 256);
-        const size_t b_mraw = align_up(sizeof(double) * kReduceRows * kMaxEntries, 256);
-        const size_t b_C = align_up(sizeof(double) * QN_MAX_M * QN_MAX_M, 256);
-        const size_t b_w = align_up(sizeof(double) * QN_MAX_M, 256);
-        const size_t b_c = align_up(sizeof(float) * QN_MAX_M, 256);
-        ws.bytes = b_part + b_mraw + 3 * b_C + 4 * b_w + 3 * b_c;
-        if (hipMalloc(&ws.base, ws.bytes) != hipSuccess) {
-            (void)hipGetLastError();
-            return QN_ENOMEM;
-        }
-        char *p = static_cast<char *>(ws.base);
-        ws.partials = reinterpret_cast<double *>(p); p += b_part;
-        ws.mraw = reinterpret_cast<double *>(p); p += b_mraw;
-        ws.C = reinterpret_cast<double *>(p); p += b_C;
-        ws.w = reinterpret_cast<double *>(p); p += b_w;
-        ws.c = reinterpret_cast<float *>(p); p += b_c;
-        ws.V = reinterpret_cast<double *>(p); p += b_C;
-        ws.sigma = reinterpret_cast<double *>(p); p += b_w;
-        ws.wz = reinterpret_cast<double *>(p); p += b_w;
-        ws.cz = reinterpret_cast<float *>(p); p += b_c;
-        ws.Ct = reinterpret_cast<double *>(p); p += b_C;
-        ws.wt = reinterpret_cast<double *>(p); p += b_w;
-        ws.tau_eff = reinterpret_cast<float *>(p); p += b_c;
-        g_ws[dev] = ws;
-        g_ws_ready[dev] = true;
+        Device d{};
+        d.cu_count = prop.multiProcessorCount;
+        g_dev[dev] = d;
+        g_dev_ready[dev] = true;
     }
-    *out = &g_ws[dev];
+    *out = &g_dev[dev];
     return QN_OK;
+}
+
+int carve_workspace(void *base, size_t bytes, int64_t n, int m, int dtype, int cu_count,
+                    Workspace *ws)
+{
+    if (base == nullptr || reinterpret_cast<uintptr_t>(base) % 256 != 0 ||
+        bytes < workspace_need(n, m, dtype, cu_count))
+        return QN_EWORKSPACE;
+    const size_t entries = static_cast<size_t>(gram_entries(m));
+    Workspace v{};
+    v.cu_count = cu_count;
+    v.max_partials = gram_max_partials(n, m, dtype, cu_count);
+    char *p = static_cast<char *>(base);
+    v.partials = reinterpret_cast<double *>(p);
+    p += ws_align(sizeof(double) * static_cast<size_t>(v.max_partials) * entries);
+    v.mraw = reinterpret_cast<double *>(p);
+    p += ws_align(sizeof(double) * kReduceRows * entries);
+    v.C = reinterpret_cast<double *>(p); p += kWsMatrixBytes;
+    v.V = reinterpret_cast<double *>(p); p += kWsMatrixBytes;
+    v.Ct = reinterpret_cast<double *>(p); p += kWsMatrixBytes;
+    v.w = reinterpret_cast<double *>(p); p += kWsVectorBytes;
+    v.sigma = reinterpret_cast<double *>(p); p += kWsVectorBytes;
+    v.wz = reinterpret_cast<double *>(p); p += kWsVectorBytes;
+    v.wt = reinterpret_cast<double *>(p); p += kWsVectorBytes;
+    v.c = reinterpret_cast<float *>(p); p += kWsVectorBytes;
+    v.cz = reinterpret_cast<float *>(p); p += kWsVectorBytes;
+    v.tau_eff = reinterpret_cast<float *>(p); p += kWsVectorBytes;
+    v.c64 = reinterpret_cast<double *>(p); p += kWsVectorBytes;
+    v.cz64 = reinterpret_cast<double *>(p); p += kWsVectorBytes;
+    *ws = v;
+    return QN_OK;
+}
+
+// The largest workspace any problem needs on a device with this many units.
+static size_t workspace_max(int cu_count)
+{
+    size_t best = 0;
+    const int64_t big = static_cast<int64_t>(1) << 40;
+    for (int m = 16; m <= QN_MAX_M; m += 16)
+        for (int dt = QN_F32; dt <= QN_F16; ++dt) {
+            const size_t b = workspace_need(big, m, dt, cu_count);
+            best = b > best ? b : best;
+        }
+    return best;
+}
+
+int get_lib_workspace(int64_t n, int m, int dtype, Workspace *ws)
+{
+    Device *d = nullptr;
+    const int rc = get_device(&d);
+    if (rc != QN_OK)
+        return rc;
+    {
+        std::lock_guard<std::mutex> lock(g_dev_mutex);
+        if (d->lib_ws == nullptr) {
+            const size_t bytes = workspace_max(d->cu_count);
+            void *p = nullptr;
+            if (hipMalloc(&p, bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                return QN_ENOMEM;
+            }
+            d->lib_ws = p;
+            d->lib_ws_bytes = bytes;
+        }
+    }
+    return carve_workspace(d->lib_ws, d->lib_ws_bytes, n, m, dtype, d->cu_count, ws);
+}
+
+// A caller's buffer as the workspace of an (n, m, dtype) problem on the current device.
+static int get_caller_workspace(void *base, size_t bytes, int64_t n, int m, int dtype,
+                                Workspace *ws)
+{
+    Device *d = nullptr;
+    const int rc = get_device(&d);
+    if (rc != QN_OK)
+        return rc;
+    return carve_workspace(base, bytes, n, m, dtype, d->cu_count, ws);
 }
 
 // ------------------------------------------------------------------ tracing --
@@ -73,9 +126,11 @@ struct TraceState {
     std::vector<int> kernel;
 };
 static TraceState g_trace;
+static std::mutex g_trace_mutex;
 
 TraceScope::TraceScope(int kernel_id, hipStream_t s) : slot(-1), stream(s)
 {
+    std::lock_guard<std::mutex> lock(g_trace_mutex);
     if (g_trace.enabled && g_trace.used < static_cast<int>(g_trace.start.size())) {
         slot = g_trace.used++;
         g_trace.kernel[slot] = kernel_id;
@@ -85,15 +140,37 @@ TraceScope::TraceScope(int kernel_id, hipStream_t s) : slot(-1), stream(s)
 
 TraceScope::~TraceScope()
 {
-    if (slot >= 0)
+    if (slot < 0)
+        return;
+    std::lock_guard<std::mutex> lock(g_trace_mutex);
+    if (g_trace.enabled && slot < static_cast<int>(g_trace.stop.size()))
         (void)hipEventRecord(g_trace.stop[slot], stream);
 }
 
-// --------------------------------------------------------------- validation --
-static bool bad_common(const void *a, int dtype, int64_t n, int m, int64_t ld)
+// ------------------------------------------------ the fused steps, any workspace --
+int run_update(const void *thetas, const void *grads, int dtype, int64_t n, int m,
+               int64_t ld, float tau, float lambda, float *theta_new, int *j_out,
+               Workspace *ws, hipStream_t s)
 {
-    return a == nullptr || (dtype != QN_F32 && dtype != QN_BF16 && dtype != QN_F16) || n < 1 ||
-           m < 1 || m > QN_MAX_M || ld < n;
+    RawGram raw;
+    int rc = launch_gram_raw(grads, dtype, n, m, ld, ws, nullptr, &raw, s);
+    if (rc != QN_OK)
+        return rc;
+    // with fp32 storage the apply pass takes c in double (its sums run in fp64)
+    double *c64 = dtype == QN_F32 ? ws->c64 : nullptr;
+    rc = launch_eig(nullptr, nullptr, m, lambda, nullptr, nullptr, ws->c, j_out, s, &raw, c64);
+    if (rc != QN_OK)
+        return rc;
+    return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, nullptr, tau, nullptr, theta_new,
+                        ws->cu_count, s, c64);
+}
+
+static bool bad_update_args(const void *thetas, const void *grads, int dtype, int64_t n,
+                            int m, int64_t ld, float tau, float lambda,
+                            const float *theta_new, const int *j_out)
+{
+    return bad_matrix_args(thetas, dtype, n, m, ld) || !grads || !theta_new || !j_out ||
+           !std::isfinite(tau) || !std::isfinite(lambda) || !(lambda > 0.0f);
 }
 
 }  // namespace qn
@@ -110,6 +187,7 @@ const char *qn_status_string(int status)
     case QN_ENOMEM: return "workspace allocation failed";
     case QN_ELAUNCH: return "HIP call or kernel launch failed";
     case QN_EARCH: return "device is not gfx950";
+    case QN_EWORKSPACE: return "workspace missing, misaligned or too small";
     default: return "unknown status";
     }
 }
@@ -130,37 +208,77 @@ const char *qn_kernel_name(int kernel_id)
 
 int qn_init(void)
 {
-    Workspace *ws = nullptr;
-    return get_workspace(&ws);
+    Workspace ws;
+    return get_lib_workspace(1, 1, QN_F32, &ws);
 }
 
 int qn_shutdown(void)
 {
-    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
     int cur = 0;
     if (hipGetDevice(&cur) != hipSuccess)
         return QN_ELAUNCH;
     int rc = QN_OK;
     for (int d = 0; d < kMaxDevices; ++d)
-        if (g_ws_ready[d]) {
-            if (hipSetDevice(d) != hipSuccess || hipFree(g_ws[d].base) != hipSuccess)
+        if (g_dev_ready[d] && g_dev[d].lib_ws != nullptr) {
+            if (hipSetDevice(d) != hipSuccess || hipFree(g_dev[d].lib_ws) != hipSuccess)
                 rc = QN_ELAUNCH;
-            g_ws_ready[d] = false;
+            g_dev[d].lib_ws = nullptr;
+            g_dev[d].lib_ws_bytes = 0;
         }
     (void)hipSetDevice(cur);
     return rc;
 }
 
+size_t qn_workspace_bytes(int64_t n, int m, int dtype)
+{
+    if (n < 1 || m < 1 || m > QN_MAX_M ||
+        (dtype != QN_F32 && dtype != QN_BF16 && dtype != QN_F16))
+        return 0;
+    int cu = 256;
+    Device *d = nullptr;
+    if (get_device(&d) == QN_OK)
+        cu = d->cu_count;
+    return workspace_need(n, m, dtype, cu);
+}
+
 int qn_gram_ex(const void *grads, int dtype, int64_t n, int m, int64_t ld,
                double *C, double *w, qn_stream_t stream)
 {
-    if (bad_common(grads, dtype, n, m, ld) || !C || !w)
+    if (bad_matrix_args(grads, dtype, n, m, ld) || !C || !w)
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    const int rc = get_workspace(&ws);
+    Workspace ws;
+    const int rc = get_lib_workspace(n, m, dtype, &ws);
     if (rc != QN_OK)
         return rc;
-    return launch_gram(grads, dtype, n, m, ld, ws, nullptr, C, w, static_cast<hipStream_t>(stream));
+    return launch_gram(grads, dtype, n, m, ld, &ws, nullptr, C, w, static_cast<hipStream_t>(stream));
+}
+
+int qn_gram_ws(const void *grads, int dtype, int64_t n, int m, int64_t ld, double *C,
+               double *w, void *workspace, size_t workspace_bytes, qn_stream_t stream)
+{
+    if (bad_matrix_args(grads, dtype, n, m, ld) || !C || !w)
+        return QN_EINVAL;
+    Workspace ws;
+    const int rc = get_caller_workspace(workspace, workspace_bytes, n, m, dtype, &ws);
+    if (rc != QN_OK)
+        return rc;
+    return launch_gram(grads, dtype, n, m, ld, &ws, nullptr, C, w, static_cast<hipStream_t>(stream));
+}
+
+int qn_diag_gram_ex(const void *grads, int dtype, const float *z, int64_t n, int m,
+                    int64_t ld, int path, double *C, double *w, qn_stream_t stream)
+{
+    if (bad_matrix_args(grads, dtype, n, m, ld) || !C || !w ||
+        (path != QN_GRAM_AUTO && path != QN_GRAM_STREAM && path != QN_GRAM_SMALL) ||
+        (path == QN_GRAM_SMALL && n > (static_cast<int64_t>(1) << 22)))
+        return QN_EINVAL;
+    // a workspace that serves either kernel at any n: laid out for the largest grid
+    Workspace ws;
+    int rc = get_lib_workspace(static_cast<int64_t>(1) << 40, m, dtype, &ws);
+    if (rc != QN_OK)
+        return rc;
+    return launch_gram(grads, dtype, n, m, ld, &ws, z, C, w, static_cast<hipStream_t>(stream), path);
 }
 
 int qn_eig(const double *C, const double *w, int m, float lambda, double *sigma,
@@ -169,8 +287,8 @@ int qn_eig(const double *C, const double *w, int m, float lambda, double *sigma,
     if (!C || !w || !c || !j_out || m < 1 || m > QN_MAX_M ||
         !std::isfinite(lambda) || !(lambda > 0.0f))
         return QN_EINVAL;
-    Workspace *ws = nullptr;   // arch check only
-    const int rc = get_workspace(&ws);
+    Device *d = nullptr;   // architecture check and kernel set-up
+    const int rc = get_device(&d);
     if (rc != QN_OK)
         return rc;
     return launch_eig(C, w, m, lambda, sigma, V, c, j_out, static_cast<hipStream_t>(stream));
@@ -180,38 +298,43 @@ int qn_apply_ex(const void *thetas, const void *grads, int dtype, int64_t n,
                 int m, int64_t ld, const float *c, float tau, float *theta_new,
                 qn_stream_t stream)
 {
-    if (bad_common(thetas, dtype, n, m, ld) || !grads || !c || !theta_new ||
+    if (bad_matrix_args(thetas, dtype, n, m, ld) || !grads || !c || !theta_new ||
         !std::isfinite(tau))
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    const int rc = get_workspace(&ws);
+    Device *d = nullptr;
+    const int rc = get_device(&d);
     if (rc != QN_OK)
         return rc;
     return launch_apply(thetas, grads, dtype, n, m, ld, c, nullptr, tau, nullptr, theta_new,
-                        ws->cu_count, static_cast<hipStream_t>(stream));
+                        d->cu_count, static_cast<hipStream_t>(stream));
 }
 
 int qn_update_ex(const void *thetas, const void *grads, int dtype, int64_t n,
                  int m, int64_t ld, float tau, float lambda, float *theta_new,
                  int *j_out, qn_stream_t stream)
 {
-    if (bad_common(thetas, dtype, n, m, ld) || !grads || !theta_new || !j_out ||
-        !std::isfinite(tau) || !std::isfinite(lambda) || !(lambda > 0.0f))
+    if (bad_update_args(thetas, grads, dtype, n, m, ld, tau, lambda, theta_new, j_out))
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    int rc = get_workspace(&ws);
+    Workspace ws;
+    const int rc = get_lib_workspace(n, m, dtype, &ws);
     if (rc != QN_OK)
         return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    RawGram raw;
-    rc = launch_gram_raw(grads, dtype, n, m, ld, ws, nullptr, &raw, s);
+    return run_update(thetas, grads, dtype, n, m, ld, tau, lambda, theta_new, j_out, &ws,
+                      static_cast<hipStream_t>(stream));
+}
+
+int qn_update_ws(const void *thetas, const void *grads, int dtype, int64_t n, int m,
+                 int64_t ld, float tau, float lambda, float *theta_new, int *j_out,
+                 void *workspace, size_t workspace_bytes, qn_stream_t stream)
+{
+    if (bad_update_args(thetas, grads, dtype, n, m, ld, tau, lambda, theta_new, j_out))
+        return QN_EINVAL;
+    Workspace ws;
+    const int rc = get_caller_workspace(workspace, workspace_bytes, n, m, dtype, &ws);
     if (rc != QN_OK)
         return rc;
-    rc = launch_eig(nullptr, nullptr, m, lambda, nullptr, nullptr, ws->c, j_out, s, &raw);
-    if (rc != QN_OK)
-        return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, nullptr, tau, nullptr, theta_new,
-                        ws->cu_count, s);
+    return run_update(thetas, grads, dtype, n, m, ld, tau, lambda, theta_new, j_out, &ws,
+                      static_cast<hipStream_t>(stream));
 }
 
 int qn_update(const float *thetas, const float *grads, int64_t n, int m,
@@ -255,6 +378,7 @@ int qn_apply_bf16(const uint16_t *thetas, const uint16_t *grads, int64_t n,
 
 int qn_trace_begin(int max_launches)
 {
+    std::lock_guard<std::mutex> lock(g_trace_mutex);
     if (max_launches < 1 || g_trace.enabled)
         return QN_EINVAL;
     g_trace.start.resize(max_launches);
@@ -271,6 +395,7 @@ int qn_trace_begin(int max_launches)
 
 int qn_trace_end(double *ms_sum, int *launches)
 {
+    std::lock_guard<std::mutex> lock(g_trace_mutex);
     if (!g_trace.enabled || !ms_sum || !launches)
         return QN_EINVAL;
     g_trace.enabled = false;

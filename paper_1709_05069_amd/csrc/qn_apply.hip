@@ -17,6 +17,11 @@
 //     (Theta - G) c = sum_k c_k (t_k - h_k) - (St - Sh)/m * sum_k c_k
 // which equals the centred definition for any c (the last term vanishes when
 // the entries of c sum to zero, as they do when c comes from the eigen step).
+// With fp32 storage the sum over k and the final combination run in fp64: when
+// g_bar lies (almost) inside span{u_1..u_j} -- always for n < m -- the term G c
+// cancels g_bar, and an fp32 sum would leave an error of 2^-24 |g_bar| in a
+// result that can be a hundred times smaller.  The kernel is bound by HBM
+// bandwidth, so the two extra fp64 operations per element are free.
 //
 // Operator mode (z != nullptr): the same sweep evaluates eq. (4) for an
 // arbitrary vector z, out = z + (Theta - G) c_z with c_z built from G^T z, and
@@ -33,7 +38,6 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef v4f v4f_elem __attribute__((aligned(4)));
 typedef v4u v4u_elem __attribute__((aligned(2)));
 
-constexpr int kApplyThreads = 256;
 // worker columns whose loads are issued together (two such chunks are in flight)
 #ifndef QN_APPLY_CHUNK_F32
 #define QN_APPLY_CHUNK_F32 8
@@ -46,6 +50,34 @@ constexpr int kApplyThreads = 256;
 #ifndef QN_APPLY_BF16_RAW
 #define QN_APPLY_BF16_RAW 1
 #endif
+// Type of the sum over the workers: fp64 for fp32 storage (see the header), fp32
+// for the 16-bit storage types, whose own resolution is far coarser.
+template <int DT> struct ApplyAcc { using type = float; };
+template <> struct ApplyAcc<QN_F32> { using type = double; };
+__device__ __forceinline__ float fma_acc(float a, float b, float c) { return fmaf(a, b, c); }
+__device__ __forceinline__ double fma_acc(double a, float b, double c)
+{
+    return fma(a, static_cast<double>(b), c);
+}
+// c_k: from the double vector when there is one (fp32 storage, fused steps)
+template <typename Acc>
+__device__ __forceinline__ Acc coef_at(const float *__restrict__ c,
+                                       const double *__restrict__ c64, int k)
+{
+    if constexpr (sizeof(Acc) == sizeof(double))
+        return c64 != nullptr ? c64[k] : static_cast<double>(c[k]);
+    else
+        return c[k];
+}
+template <typename Acc>
+__device__ __forceinline__ Acc coef_sum(const float *__restrict__ c,
+                                        const double *__restrict__ c64, int m)
+{
+    Acc s = 0;
+    for (int k = 0; k < m; ++k)
+        s += coef_at<Acc>(c, c64, k);
+    return s;
+}
 template <int DT> struct ApplyChunk {
     static constexpr int value = DT == QN_F32 ? QN_APPLY_CHUNK_F32 : QN_APPLY_CHUNK_BF16;
 };
@@ -124,8 +156,10 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
                                              const void *__restrict__ grads,
                                              int64_t row, int m_rt, int64_t ld,
                                              const float *__restrict__ c,
+                                             const double *__restrict__ c64,
                                              const float *__restrict__ z,
-                                             float csum, float tau, float inv_m,
+                                             typename ApplyAcc<DT>::type csum,
+                                             float tau, float inv_m,
                                              float (&res)[R])
 {
     constexpr int kApplyChunk = ApplyChunk<DT>::value;
@@ -136,7 +170,9 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
     // per byte).  fp32 storage keeps the pivot form.
     constexpr bool RAW = DT != QN_F32 && QN_APPLY_BF16_RAW;
     const int m = MC ? MC : m_rt;
-    float p[R], r[R], st[R], sh[R], acc[R];
+    using Acc = typename ApplyAcc<DT>::type;   // double for fp32 storage
+    float p[R], r[R], st[R], sh[R];
+    Acc acc[R];
     load_vec<DT, R>(thetas, row, p);
     load_vec<DT, R>(grads, row, r);
     const float c0 = RAW ? c[0] : 0.0f;
@@ -171,7 +207,7 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
 #pragma unroll
         for (int u = 0; u < kApplyChunk; ++u)
             if (k0 + u < m) {
-                const float ck = c[k0 + u];
+                const Acc ck = coef_at<Acc>(c, c64, k0 + u);
                 float tv[R], gv[R];
                 unpack_rows<DT, R>(th[u], tv);
                 unpack_rows<DT, R>(gr[u], gv);
@@ -181,7 +217,7 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
                     const float h = RAW ? gv[e] : gv[e] - r[e];
                     st[e] += t;
                     sh[e] += h;
-                    acc[e] = fmaf(ck, t - h, acc[e]);
+                    acc[e] = fma_acc(ck, t - h, acc[e]);
                 }
             }
 #pragma unroll
@@ -205,11 +241,18 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
 #pragma unroll
     for (int e = 0; e < R; ++e) {
         const float mt = st[e] * inv_m, mh = sh[e] * inv_m;
-        const float corr = acc[e] - csum * (mt - mh);
-        if constexpr (RAW)      // mt, mh are theta_bar, g_bar themselves
+        if constexpr (RAW) {    // mt, mh are theta_bar, g_bar themselves
+            const float corr = acc[e] - csum * (mt - mh);
             res[e] = z != nullptr ? zz[e] + corr : mt - tau * (mh + corr);
-        else
-            res[e] = z != nullptr ? zz[e] + corr : (p[e] + mt) - tau * ((r[e] + mh) + corr);
+        } else {
+            // fp64 from here on: (r + mh) + corr is where g_bar meets - G c
+            const double corr = acc[e] - csum * (static_cast<double>(mt) - mh);
+            const double v = z != nullptr
+                ? zz[e] + corr
+                : (static_cast<double>(p[e]) + mt) -
+                      static_cast<double>(tau) * ((static_cast<double>(r[e]) + mh) + corr);
+            res[e] = static_cast<float>(v);
+        }
     }
 }
 
@@ -219,12 +262,14 @@ __device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
                                            const void *__restrict__ grads,
                                            int64_t row, int m_rt, int64_t ld,
                                            const float *__restrict__ c,
+                                           const double *__restrict__ c64,
                                            const float *__restrict__ z,
-                                           float csum, float tau, float inv_m,
+                                           typename ApplyAcc<DT>::type csum,
+                                           float tau, float inv_m,
                                            float *__restrict__ out)
 {
     float res[R];
-    compute_rows<DT, MC, R>(thetas, grads, row, m_rt, ld, c, z, csum, tau, inv_m, res);
+    compute_rows<DT, MC, R>(thetas, grads, row, m_rt, ld, c, c64, z, csum, tau, inv_m, res);
     if constexpr (R == 1) {
         out[row] = res[0];
     } else {
@@ -239,28 +284,27 @@ __device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
 template <int DT, int MC, bool VEC>
 __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
     const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
-    int m_rt, int64_t ld, const float *__restrict__ c,
+    int m_rt, int64_t ld, const float *__restrict__ c, const double *__restrict__ c64,
     const float *__restrict__ z, float tau_host, const float *__restrict__ tau_dev,
     float *__restrict__ out)
 {
     constexpr int R = VEC ? (DT == QN_F32 ? 4 : 8) : 1;
     const int m = MC ? MC : m_rt;
     const float tau = tau_dev != nullptr ? *tau_dev : tau_host;   // uniform
-    float csum = 0.0f;
-    for (int k = 0; k < m; ++k)
-        csum += c[k];
+    using Acc = typename ApplyAcc<DT>::type;
+    const Acc csum = coef_sum<Acc>(c, c64, m);
     const float inv_m = 1.0f / static_cast<float>(m);
 
     const int64_t nvec = n / R;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kApplyThreads;
     for (int64_t v = static_cast<int64_t>(blockIdx.x) * kApplyThreads + threadIdx.x;
          v < nvec; v += stride)
-        apply_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, z, csum, tau, inv_m, out);
+        apply_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, c64, z, csum, tau, inv_m, out);
 
     if constexpr (R > 1) {   // rows past the last full vector
         const int64_t tail0 = nvec * R;
         if (blockIdx.x == 0 && tail0 + threadIdx.x < n)
-            apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c, z,
+            apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c, c64, z,
                                   csum, tau, inv_m, out);
     }
 }
@@ -271,34 +315,16 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
 // it is computed, 0.26 ms when each CU writes 128 KiB bursts).  So one block
 // per CU keeps a slab of results in LDS and writes it out in one contiguous
 // burst.  Same arithmetic, same bits as apply_kernel.
-#ifndef QN_STAGED_THREADS_F32
-#define QN_STAGED_THREADS_F32 256
-#endif
-#ifndef QN_STAGED_THREADS_BF16
-#define QN_STAGED_THREADS_BF16 1024
-#endif
 // block size of the staged variant: fp32 streams best with few waves per CU;
-// bf16 has twice the arithmetic per byte and needs more waves to hide it
+// 16-bit storage has twice the arithmetic per byte and needs more waves to hide it
 template <int DT> struct StagedThreads {
-    static constexpr int value = DT == QN_F32 ? QN_STAGED_THREADS_F32 : QN_STAGED_THREADS_BF16;
+    static constexpr int value = staged_threads(DT);
 };
-#ifndef QN_STAGED_BLOCKS_PER_CU
-#define QN_STAGED_BLOCKS_PER_CU 1
-#endif
-#ifndef QN_STAGED_LDS_KB
-#define QN_STAGED_LDS_KB 128
-#endif
-constexpr int kStagedLdsBytes = QN_STAGED_LDS_KB * 1024;
-
-template <int DT> constexpr int staged_max_steps()
-{
-    return kStagedLdsBytes / (StagedThreads<DT>::value * 16 * (DT == QN_F32 ? 1 : 2));
-}
 
 template <int DT, int MC>
 __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
     const void *__restrict__ thetas, const void *__restrict__ grads, int64_t n,
-    int m_rt, int64_t ld, const float *__restrict__ c,
+    int m_rt, int64_t ld, const float *__restrict__ c, const double *__restrict__ c64,
     const float *__restrict__ z, float tau_host, const float *__restrict__ tau_dev,
     float *__restrict__ out, int steps)
 {
@@ -306,12 +332,11 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
     constexpr int kStagedThreads = StagedThreads<DT>::value;
     constexpr int R = DT == QN_F32 ? 4 : 8;        // rows per lane per step
     constexpr int Q = R / 4;                       // 128-bit results per lane per step
-    // steps <= staged_max_steps<DT>(): lane-steps per thread per slab
+    // steps <= staged_max_steps(DT): lane-steps per thread per slab
     extern __shared__ v4f stage[];
     const int m = MC ? MC : m_rt;
-    float csum = 0.0f;
-    for (int k = 0; k < m; ++k)
-        csum += c[k];
+    using Acc = typename ApplyAcc<DT>::type;
+    const Acc csum = coef_sum<Acc>(c, c64, m);
     const float inv_m = 1.0f / static_cast<float>(m);
 
     const int64_t nvec = n / R;
@@ -324,7 +349,7 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
             const int64_t v = base + static_cast<int64_t>(it) * kStagedThreads + threadIdx.x;
             if (v < nvec) {
                 float res[R];
-                compute_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, z, csum, tau, inv_m, res);
+                compute_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, c64, z, csum, tau, inv_m, res);
 #pragma unroll
                 for (int h = 0; h < Q; ++h)
                     stage[(it * kStagedThreads + threadIdx.x) * Q + h] =
@@ -344,48 +369,41 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
 
     const int64_t tail0 = nvec * R;                // rows past the last full vector
     if (blockIdx.x == 0 && tail0 + threadIdx.x < n)
-        apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c, z, csum,
+        apply_rows<DT, MC, 1>(thetas, grads, tail0 + threadIdx.x, m_rt, ld, c, c64, z, csum,
                               tau, inv_m, out);
 }
 
-enum class ApplyShape { kElementwise, kDirect, kStaged };
-
 template <int DT, int MC>
-static void launch_mc(ApplyShape shape, int grid, const void *thetas, const void *grads,
-                      int64_t n, int m, int64_t ld, const float *c, const float *z, float tau,
-                      const float *tau_dev, float *out, hipStream_t stream)
+static void launch_mc(const ApplyPlan &plan, const void *thetas, const void *grads,
+                      int64_t n, int m, int64_t ld, const float *c, const double *c64,
+                      const float *z, float tau, const float *tau_dev, float *out,
+                      hipStream_t stream)
 {
-    if (shape == ApplyShape::kStaged) {
-        // slab length: every block gets the same number of (nearly) full slabs
-        constexpr int R = DT == QN_F32 ? 4 : 8;
-        const int64_t lanes = static_cast<int64_t>(grid) * StagedThreads<DT>::value;
-        const int64_t per_thread = (n / R + lanes - 1) / lanes;            // lane-steps
-        const int64_t rounds = (per_thread + staged_max_steps<DT>() - 1) / staged_max_steps<DT>();
-        const int steps = static_cast<int>((per_thread + rounds - 1) / rounds);
-        hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(grid), dim3(StagedThreads<DT>::value),
-                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, steps);
-        return;
-    }
-    if (shape == ApplyShape::kDirect)
-        hipLaunchKernelGGL((apply_kernel<DT, MC, true>), dim3(grid), dim3(kApplyThreads),
-                           0, stream, thetas, grads, n, m, ld, c, z, tau, tau_dev, out);
+    if (plan.shape == kApplyStaged)
+        hipLaunchKernelGGL((apply_staged<DT, MC>), dim3(plan.grid), dim3(StagedThreads<DT>::value),
+                           kStagedLdsBytes, stream, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev,
+                           out, plan.steps);
+    else if (plan.shape == kApplyDirect)
+        hipLaunchKernelGGL((apply_kernel<DT, MC, true>), dim3(plan.grid), dim3(kApplyThreads),
+                           0, stream, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, out);
     else
-        hipLaunchKernelGGL((apply_kernel<DT, MC, false>), dim3(grid), dim3(kApplyThreads),
-                           0, stream, thetas, grads, n, m, ld, c, z, tau, tau_dev, out);
+        hipLaunchKernelGGL((apply_kernel<DT, MC, false>), dim3(plan.grid), dim3(kApplyThreads),
+                           0, stream, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, out);
 }
 
 template <int DT>
-static void launch_dt(ApplyShape shape, int grid, const void *thetas, const void *grads,
-                      int64_t n, int m, int64_t ld, const float *c, const float *z, float tau,
-                      const float *tau_dev, float *out, hipStream_t stream)
+static void launch_dt(const ApplyPlan &plan, const void *thetas, const void *grads,
+                      int64_t n, int m, int64_t ld, const float *c, const double *c64,
+                      const float *z, float tau, const float *tau_dev, float *out,
+                      hipStream_t stream)
 {
     switch (m) {
-    case 4: launch_mc<DT, 4>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
-    case 8: launch_mc<DT, 8>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
-    case 16: launch_mc<DT, 16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
-    case 32: launch_mc<DT, 32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
-    case 64: launch_mc<DT, 64>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
-    default: launch_mc<DT, 0>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, out, stream); break;
+    case 4: launch_mc<DT, 4>(plan, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, out, stream); break;
+    case 8: launch_mc<DT, 8>(plan, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, out, stream); break;
+    case 16: launch_mc<DT, 16>(plan, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, out, stream); break;
+    case 32: launch_mc<DT, 32>(plan, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, out, stream); break;
+    case 64: launch_mc<DT, 64>(plan, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, out, stream); break;
+    default: launch_mc<DT, 0>(plan, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, out, stream); break;
     }
 }
 
@@ -409,33 +427,18 @@ int setup_apply_kernels()
 
 int launch_apply(const void *thetas, const void *grads, int dtype, int64_t n,
                  int m, int64_t ld, const float *c, const float *z, float tau,
-                 const float *tau_dev, float *theta_new, int cu_count, hipStream_t stream)
+                 const float *tau_dev, float *theta_new, int cu_count, hipStream_t stream,
+                 const double *c64)
 {
-    // 128-bit accesses work at element alignment (see v4f_elem), so the wide path
-    // serves every input; the element-wise kernel remains as the shape for
-    // problems smaller than one vector per lane
-    const bool vec = n >= (dtype == QN_F32 ? 4 : 8);
-    const int rows_per_thread = vec ? (dtype == QN_F32 ? 4 : 8) : 1;
-    const int64_t per_block = static_cast<int64_t>(kApplyThreads) * rows_per_thread;
-    int64_t want = (n + per_block - 1) / per_block;
-    const int64_t cap = static_cast<int64_t>(cu_count) * 8;
-    int grid = static_cast<int>(want < cap ? want : cap);
-    ApplyShape shape = vec ? ApplyShape::kDirect : ApplyShape::kElementwise;
-    // large aligned problems: one block per CU with LDS-staged output bursts
-    // (a full slab covers 32768 rows; worth it once every CU gets at least one)
-    const int64_t slab_rows = kStagedLdsBytes / 4;
-    if (vec && n >= slab_rows * cu_count) {
-        shape = ApplyShape::kStaged;
-        grid = cu_count * QN_STAGED_BLOCKS_PER_CU;
-    }
-
+    // launch shape, grid and slab length: a function of (n, dtype, CU count) only
+    const ApplyPlan plan = apply_plan(n, dtype, cu_count);
     TraceScope ts(QN_K_APPLY, stream);
     if (dtype == QN_F32)
-        launch_dt<QN_F32>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, theta_new, stream);
+        launch_dt<QN_F32>(plan, thetas, grads, n, m, ld, c, c64, z, tau, tau_dev, theta_new, stream);
     else if (dtype == QN_BF16)
-        launch_dt<QN_BF16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, theta_new, stream);
+        launch_dt<QN_BF16>(plan, thetas, grads, n, m, ld, c, nullptr, z, tau, tau_dev, theta_new, stream);
     else
-        launch_dt<QN_F16>(shape, grid, thetas, grads, n, m, ld, c, z, tau, tau_dev, theta_new, stream);
+        launch_dt<QN_F16>(plan, thetas, grads, n, m, ld, c, nullptr, z, tau, tau_dev, theta_new, stream);
     return check_launch();
 }
 

@@ -69,6 +69,41 @@ int launch_tau_bound(int mode, float tau, const double *sigma, const double *V,
     return check_launch();
 }
 
+int run_update_bounded(const void *thetas, const void *grads, int dtype, int64_t n, int m,
+                       int64_t ld, float tau, float lambda, int mode, float *theta_new,
+                       int *j_out, float *tau_out, Workspace *ws, hipStream_t s)
+{
+    RawGram raw;
+    int rc = launch_gram_raw(grads, dtype, n, m, ld, ws, nullptr, &raw, s);
+    if (rc != QN_OK)
+        return rc;
+    double *c64 = dtype == QN_F32 ? ws->c64 : nullptr;
+    rc = launch_eig(nullptr, nullptr, m, lambda, ws->sigma, ws->V, ws->c, j_out, s, &raw, c64);
+    if (rc != QN_OK)
+        return rc;
+    if (mode == QN_BOUND_SECANT) {
+        // Theta^T Theta by the same centred Gram pass, over the theta columns
+        rc = launch_gram(thetas, dtype, n, m, ld, ws, nullptr, ws->Ct, ws->wt, s);
+        if (rc != QN_OK)
+            return rc;
+    }
+    float *tau_dev = tau_out ? tau_out : ws->tau_eff;
+    rc = launch_tau_bound(mode, tau, ws->sigma, ws->V, j_out, ws->Ct, m, tau_dev, nullptr, s);
+    if (rc != QN_OK)
+        return rc;
+    return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, nullptr, tau, tau_dev,
+                        theta_new, ws->cu_count, s, c64);
+}
+
+static bool bad_bounded_args(const void *thetas, const void *grads, int dtype, int64_t n,
+                             int m, int64_t ld, float tau, float lambda, int mode,
+                             const float *theta_new, const int *j_out)
+{
+    return bad_matrix_args(thetas, dtype, n, m, ld) || !grads || !theta_new || !j_out ||
+           !std::isfinite(tau) || !std::isfinite(lambda) || !(lambda > 0.0f) ||
+           (mode != QN_BOUND_SIGMA1 && mode != QN_BOUND_SECANT);
+}
+
 }  // namespace qn
 
 using namespace qn;
@@ -83,8 +118,8 @@ int qn_tau_bound(const double *sigma, const double *V, const int *j,
         (mode != QN_BOUND_SIGMA1 && mode != QN_BOUND_SECANT) ||
         (mode == QN_BOUND_SECANT && !C_theta))
         return QN_EINVAL;
-    Workspace *ws = nullptr;   // arch check only
-    const int rc = get_workspace(&ws);
+    Device *d = nullptr;   // architecture check
+    const int rc = get_device(&d);
     if (rc != QN_OK)
         return rc;
     return launch_tau_bound(mode, tau, sigma, V, j, C_theta, m, tau_out, sigma_max_out,
@@ -96,35 +131,33 @@ int qn_update_bounded_ex(const void *thetas, const void *grads, int dtype, int64
                          float *theta_new, int *j_out, float *tau_out,
                          qn_stream_t stream)
 {
-    if (!thetas || !grads || (dtype != QN_F32 && dtype != QN_BF16 && dtype != QN_F16) || n < 1 || m < 1 ||
-        m > QN_MAX_M || ld < n || !theta_new || !j_out || !std::isfinite(tau) ||
-        !std::isfinite(lambda) || !(lambda > 0.0f) ||
-        (mode != QN_BOUND_SIGMA1 && mode != QN_BOUND_SECANT))
+    if (bad_bounded_args(thetas, grads, dtype, n, m, ld, tau, lambda, mode, theta_new, j_out))
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    int rc = get_workspace(&ws);
+    Workspace ws;
+    const int rc = get_lib_workspace(n, m, dtype, &ws);
     if (rc != QN_OK)
         return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    RawGram raw;
-    rc = launch_gram_raw(grads, dtype, n, m, ld, ws, nullptr, &raw, s);
+    return run_update_bounded(thetas, grads, dtype, n, m, ld, tau, lambda, mode, theta_new,
+                              j_out, tau_out, &ws, static_cast<hipStream_t>(stream));
+}
+
+int qn_update_bounded_ws(const void *thetas, const void *grads, int dtype, int64_t n,
+                         int m, int64_t ld, float tau, float lambda, int mode,
+                         float *theta_new, int *j_out, float *tau_out, void *workspace,
+                         size_t workspace_bytes, qn_stream_t stream)
+{
+    if (bad_bounded_args(thetas, grads, dtype, n, m, ld, tau, lambda, mode, theta_new, j_out))
+        return QN_EINVAL;
+    Device *d = nullptr;
+    int rc = get_device(&d);
     if (rc != QN_OK)
         return rc;
-    rc = launch_eig(nullptr, nullptr, m, lambda, ws->sigma, ws->V, ws->c, j_out, s, &raw);
+    Workspace ws;
+    rc = carve_workspace(workspace, workspace_bytes, n, m, dtype, d->cu_count, &ws);
     if (rc != QN_OK)
         return rc;
-    if (mode == QN_BOUND_SECANT) {
-        // Theta^T Theta by the same centred Gram pass, over the theta columns
-        rc = launch_gram(thetas, dtype, n, m, ld, ws, nullptr, ws->Ct, ws->wt, s);
-        if (rc != QN_OK)
-            return rc;
-    }
-    float *tau_dev = tau_out ? tau_out : ws->tau_eff;
-    rc = launch_tau_bound(mode, tau, ws->sigma, ws->V, j_out, ws->Ct, m, tau_dev, nullptr, s);
-    if (rc != QN_OK)
-        return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, ws->c, nullptr, tau, tau_dev,
-                        theta_new, ws->cu_count, s);
+    return run_update_bounded(thetas, grads, dtype, n, m, ld, tau, lambda, mode, theta_new,
+                              j_out, tau_out, &ws, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -116,7 +116,8 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
     const double *__restrict__ C, const double *__restrict__ w, int m,
     double lambda, double *__restrict__ sigma_out, double *__restrict__ V_out,
     float *__restrict__ c_out, int *__restrict__ j_out,
-    const double *__restrict__ mraw, int entries, int z_mode, int pack)
+    const double *__restrict__ mraw, int entries, int z_mode, int pack,
+    double *__restrict__ c64_out)
 {
     constexpr int NP = M / 2;          // pairs per round
     constexpr int ROUNDS = M - 1;
@@ -186,6 +187,8 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
         const double qnan = __longlong_as_double(0x7ff8000000000000LL);
         if (tid < m) {
             c_out[tid] = 0.0f;
+            if (c64_out)
+                c64_out[tid] = 0.0;
             if (sigma_out)
                 sigma_out[tid] = qnan;
         }
@@ -368,6 +371,8 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
             mean += cvec[r];
         mean /= m;
         c_out[tid] = static_cast<float>(cvec[tid] - mean);
+        if (c64_out)
+            c64_out[tid] = cvec[tid] - mean;
         if (sigma_out)
             sigma_out[tid] = sig[tid];
     }
@@ -380,7 +385,7 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
 
 int launch_eig(const double *C, const double *w, int m, float lambda,
                double *sigma, double *V, float *c, int *j_out,
-               hipStream_t stream, const RawGram *raw)
+               hipStream_t stream, const RawGram *raw, double *c64)
 {
     const double *mraw = raw ? raw->mraw : nullptr;
     const int entries = raw ? raw->entries : 0, z_mode = raw ? raw->z_mode : 0,
@@ -394,7 +399,7 @@ int launch_eig(const double *C, const double *w, int m, float lambda,
 #define QN_EIG_LAUNCH(MM)                                                            \
     hipLaunchKernelGGL(eig_select<MM>, dim3(1), dim3(eig_threads<MM>()),             \
                        eig_lds_bytes<MM>(), stream, C, w, m, lam, sigma, V, c, j_out,   \
-                       mraw, entries, z_mode, pack)
+                       mraw, entries, z_mode, pack, c64)
     if (m <= 2) QN_EIG_LAUNCH(2);
     else if (m <= 4) QN_EIG_LAUNCH(4);
     else if (m <= 8) QN_EIG_LAUNCH(8);

@@ -65,17 +65,16 @@ template <int NT> struct GramTiles { static constexpr int value = NT * (NT + 1) 
 // A column slot is 1 KiB of one column (ROWS rows) at slot * kColPitch in LDS
 // (1 KiB + 16 B, which spreads the 16 columns a quarter-wave reads over all
 // banks).  16 * NT slots per stage, two stages.
-constexpr int kColPitch = 1040;                       // bytes per column slot
 // A pass that also carries a vector z (below) keeps z's rows of the tile in
 // ZSLOTS further slots of each stage (fp32: 1 KiB per 256 rows).
-template <int NT, int ZSLOTS> constexpr int stage_bytes() { return (16 * NT + ZSLOTS) * kColPitch; }
-template <int NT, int ZSLOTS> constexpr int stream_lds_bytes() { return 2 * stage_bytes<NT, ZSLOTS>(); }
+template <int NT, int ZSLOTS> constexpr int stage_bytes() { return gram_stage_bytes(NT, ZSLOTS); }
+template <int NT, int ZSLOTS> constexpr int stream_lds_bytes() { return gram_lds_bytes(NT, ZSLOTS); }
 
 // Rows per column slot.  bf16 inputs that are not 16-byte aligned arrive through
 // 2-byte direct-to-LDS loads, which the hardware stores zero-extended, one per
 // dword: their LDS format is 4 bytes per row.
 template <int DT, bool ALIGNED> struct StreamRows {
-    static constexpr int value = (DT == QN_F32 || !ALIGNED) ? 256 : 512;
+    static constexpr int value = gram_slot_rows(DT, ALIGNED);
 };
 
 // 16 bytes of one column from LDS as fp32 row values.  FMT 0: fp32 (4 rows);
@@ -532,45 +531,146 @@ __global__ __launch_bounds__(kProjectThreads) void gram_project(
         [&](int k, double v) { w[k] = v; });
 }
 
-// Blocks of one kernel instance that fit a CU: LDS (160 KiB) and 32 waves.
-constexpr int blocks_per_cu(int lds_bytes)
+// ---------------------------------------------------------------------------
+// The fp64 vector kernel for small problems (gram_is_small): the same pivot-shifted
+// matrix Q = D^T D, with every difference, product and sum in fp64 (differences and
+// products of fp32 or 16-bit inputs are exact there), written in the same raw
+// layout so that the reduction and the m x m algebra downstream do not change.
+// With few rows the fp32 tile sums of the matrix-core pass have nothing to
+// average over, and a step whose g_bar lies inside span{u_k} (always for n < m)
+// amplifies that error; here it is of order 1e-16 instead.
+// One block per 64-row tile (grid-stride above 256 blocks); thread p of a block
+// owns the pairs (k, l), k >= l, numbered p, p + 256, ...
+constexpr int kSmallPairsPerThread = (QN_MAX_M * (QN_MAX_M + 1) / 2 + kSmallThreads - 1) / kSmallThreads;
+
+template <int DT>
+__device__ __forceinline__ double load_elem_f64(const void *base, int64_t elem)
 {
-    const int by_lds = 163840 / lds_bytes, by_waves = 32 / kGramWaves;
-    return by_lds < by_waves ? by_lds : by_waves;
+    if constexpr (DT == QN_F32)
+        return static_cast<double>(static_cast<const float *>(base)[elem]);
+    else if constexpr (DT == QN_BF16)
+        return static_cast<double>(__uint_as_float(
+            static_cast<uint32_t>(static_cast<const uint16_t *>(base)[elem]) << 16));
+    else
+        return static_cast<double>(half_bits_to_float(static_cast<const uint16_t *>(base)[elem]));
+}
+
+template <int DT>
+__global__ __launch_bounds__(kSmallThreads) void gram_small_f64(
+    const void *__restrict__ grads, int64_t n, int m, int64_t ld,
+    double *__restrict__ partials, const float *__restrict__ z, int entries)
+{
+    constexpr int TR = kSmallTileRows;
+    __shared__ double D[QN_MAX_M][TR + 1];
+    __shared__ unsigned char pk[QN_MAX_M * (QN_MAX_M + 1) / 2], pl[QN_MAX_M * (QN_MAX_M + 1) / 2];
+    const int tid = threadIdx.x;
+    const int pairs = m * (m + 1) / 2;
+    for (int k = tid; k < m; k += kSmallThreads)      // row k of the triangle starts at k (k + 1) / 2
+        for (int l = 0; l <= k; ++l) {
+            pk[k * (k + 1) / 2 + l] = static_cast<unsigned char>(k);
+            pl[k * (k + 1) / 2 + l] = static_cast<unsigned char>(l);
+        }
+    double acc[kSmallPairsPerThread];
+#pragma unroll
+    for (int i = 0; i < kSmallPairsPerThread; ++i)
+        acc[i] = 0.0;
+
+    const int64_t tiles = (n + TR - 1) / TR;
+    for (int64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const int64_t row0 = tile * TR;
+        __syncthreads();          // the previous tile has been consumed (and pk, pl are written)
+        for (int e = tid; e < m * TR; e += kSmallThreads) {
+            const int k = e / TR, r = e % TR;
+            const int64_t row = row0 + r;
+            double v = 0.0;
+            if (row < n) {
+                const double s = load_elem_f64<DT>(grads, row);          // the pivot: worker 0
+                if (k == 0)
+                    v = z != nullptr ? static_cast<double>(z[row]) : s;
+                else
+                    v = load_elem_f64<DT>(grads, k * ld + row) - s;
+            }
+            D[k][r] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kSmallPairsPerThread; ++i) {
+            const int p = tid + i * kSmallThreads;
+            if (p < pairs) {
+                const int k = pk[p], l = pl[p];
+                double s = acc[i];
+                for (int r = 0; r < TR; ++r)
+                    s = fma(D[k][r], D[l][r], s);
+                acc[i] = s;
+            }
+        }
+    }
+    // One partial per block in the raw layout (the inverse of raw_index): entry
+    // (tile, reg, lane) holds Q[16 ti + 4 (lane / 16) + reg][16 tj + lane % 16];
+    // entries that no pair k >= l, k < m maps to are zero.
+    __syncthreads();
+    double *Q = &D[0][0];            // pairs <= 2080 doubles fit D's 4160
+#pragma unroll
+    for (int i = 0; i < kSmallPairsPerThread; ++i) {
+        const int p = tid + i * kSmallThreads;
+        if (p < pairs)
+            Q[p] = acc[i];
+    }
+    __syncthreads();
+    double *out = partials + static_cast<int64_t>(blockIdx.x) * entries;
+    for (int e = tid; e < entries; e += kSmallThreads) {
+        const int tile = e / kTileEntries, reg = (e / 64) & 3, lane = e & 63;
+        int ti = 0;
+        while (tile_index(ti + 1, 0) <= tile)
+            ++ti;
+        const int tj = tile - tile_index(ti, 0);
+        const int k = 16 * ti + 4 * (lane >> 4) + reg, l = 16 * tj + (lane & 15);
+        out[e] = (k < m && l <= k) ? Q[k * (k + 1) / 2 + l] : 0.0;
+    }
+}
+
+static int launch_small(int dtype, const void *grads, int64_t n, int m, int64_t ld,
+                        double *partials, int max_partials, const float *z, int entries,
+                        hipStream_t stream)
+{
+    const int grid = gram_small_grid(n, max_partials);
+    if (dtype == QN_F32)
+        hipLaunchKernelGGL(gram_small_f64<QN_F32>, dim3(grid), dim3(kSmallThreads), 0, stream,
+                           grads, n, m, ld, partials, z, entries);
+    else if (dtype == QN_BF16)
+        hipLaunchKernelGGL(gram_small_f64<QN_BF16>, dim3(grid), dim3(kSmallThreads), 0, stream,
+                           grads, n, m, ld, partials, z, entries);
+    else
+        hipLaunchKernelGGL(gram_small_f64<QN_F16>, dim3(grid), dim3(kSmallThreads), 0, stream,
+                           grads, n, m, ld, partials, z, entries);
+    return grid;
 }
 
 template <int DT, int NT, bool AL, bool HAS_Z, int PACK>
 constexpr int instance_lds_bytes()
 {
-    return stream_lds_bytes<NT, HAS_Z ? StreamRows<DT, AL>::value * PACK / 256 : 0>();
+    return stream_lds_bytes<NT, gram_z_slots_packed(DT, AL, PACK, HAS_Z)>();
 }
 
 template <int DT, int NT, bool AL, bool HAS_Z, int PACK>
-static int launch_instance(int cu_count, const void *grads, int64_t n, int m, int64_t ld,
-                           double *partials, const float *z, hipStream_t stream)
+static int launch_instance(int cu_count, int max_partials, const void *grads, int64_t n, int m,
+                           int64_t ld, double *partials, const float *z, hipStream_t stream)
 {
     constexpr int LDS = instance_lds_bytes<DT, NT, AL, HAS_Z, PACK>();
-    const int rows = StreamRows<DT, AL>::value * PACK;
-    const int64_t num_tiles = (n + rows - 1) / rows;
-    int64_t cap = static_cast<int64_t>(cu_count) * blocks_per_cu(LDS);
-    if (cap > kGramMaxBlocks)       // the partials buffer holds this many blocks
-        cap = kGramMaxBlocks;
-    const int grid = static_cast<int>(num_tiles < cap ? num_tiles : cap);
+    const int grid = gram_stream_grid(n, m, DT, AL, HAS_Z, cu_count, max_partials);
     const int z_aligned = reinterpret_cast<uintptr_t>(z) % 16 == 0;
     hipLaunchKernelGGL((gram_stage1_stream<DT, NT, AL, HAS_Z, PACK>), dim3(grid),
                        dim3(kGramThreads), LDS, stream, grads, n, m, ld, partials, z, z_aligned);
     return grid;
 }
 
-// row blocks packed into the 16 column lanes of a single column set
-constexpr int pack_for(int m) { return m <= 4 ? 4 : (m <= 8 ? 2 : 1); }
-
 template <int DT, bool AL, bool HAS_Z>
-static int launch_stage1(int cu_count, const void *grads, int64_t n, int m, int64_t ld,
-                         double *partials, const float *z, hipStream_t stream)
+static int launch_stage1(int cu_count, int max_partials, const void *grads, int64_t n, int m,
+                         int64_t ld, double *partials, const float *z, hipStream_t stream)
 {
 #define QN_GO(NTV, PK) \
-    return launch_instance<DT, NTV, AL, HAS_Z, PK>(cu_count, grads, n, m, ld, partials, z, stream)
+    return launch_instance<DT, NTV, AL, HAS_Z, PK>(cu_count, max_partials, grads, n, m, ld, partials, z, stream)
+    static_assert(gram_pack(4) == 4 && gram_pack(8) == 2 && gram_pack(9) == 1, "pack thresholds");
     if (m <= 4) QN_GO(1, 4);
     if (m <= 8) QN_GO(1, 2);
     if (m <= 16) QN_GO(1, 1);
@@ -581,8 +681,7 @@ static int launch_stage1(int cu_count, const void *grads, int64_t n, int m, int6
 }
 
 // The streaming kernels use up to 134 KiB of dynamic LDS; the opt-in above the
-// default 64 KiB is per device and is made once when the device's workspace is
-// set up.
+// default 64 KiB is per device and is made once when the device is set up.
 template <int DT, int NT, bool AL, bool HAS_Z, int PACK>
 static bool opt_in_one()
 {
@@ -612,32 +711,37 @@ int setup_gram_kernels()
 }
 
 int launch_gram_raw(const void *grads, int dtype, int64_t n, int m, int64_t ld,
-                    Workspace *ws, const float *z, RawGram *raw, hipStream_t stream)
+                    Workspace *ws, const float *z, RawGram *raw, hipStream_t stream, int path)
 {
     const size_t esz = dtype == QN_F32 ? 4 : 2;
     const bool aligned = (reinterpret_cast<uintptr_t>(grads) % 16 == 0) &&
                          ((static_cast<uint64_t>(ld) * esz) % 16 == 0);
-    const int nt = (m + 15) / 16;
-    const int entries = nt * (nt + 1) / 2 * kTileEntries;
+    const int entries = gram_entries(m);
+    const bool small = path == kGramAuto ? gram_is_small(n) : path == kGramSmall;
 
     // the grid is a function of (n, m, dtype, alignment) and the device's CU
     // count only, so the summation tree is reproducible
     int grid;
     {
         TraceScope ts(QN_K_GRAM, stream);
-#define QN_GO(DTV, ALV, ZV) \
-    grid = launch_stage1<DTV, ALV, ZV>(ws->cu_count, grads, n, m, ld, ws->partials, z, stream)
-        if (dtype == QN_F32) {
-            if (aligned) { if (z) QN_GO(QN_F32, true, true); else QN_GO(QN_F32, true, false); }
-            else { if (z) QN_GO(QN_F32, false, true); else QN_GO(QN_F32, false, false); }
-        } else if (dtype == QN_BF16) {
-            if (aligned) { if (z) QN_GO(QN_BF16, true, true); else QN_GO(QN_BF16, true, false); }
-            else { if (z) QN_GO(QN_BF16, false, true); else QN_GO(QN_BF16, false, false); }
+        if (small) {
+            grid = launch_small(dtype, grads, n, m, ld, ws->partials, ws->max_partials, z,
+                                entries, stream);
         } else {
-            if (aligned) { if (z) QN_GO(QN_F16, true, true); else QN_GO(QN_F16, true, false); }
-            else { if (z) QN_GO(QN_F16, false, true); else QN_GO(QN_F16, false, false); }
-        }
+#define QN_GO(DTV, ALV, ZV) \
+    grid = launch_stage1<DTV, ALV, ZV>(ws->cu_count, ws->max_partials, grads, n, m, ld, ws->partials, z, stream)
+            if (dtype == QN_F32) {
+                if (aligned) { if (z) QN_GO(QN_F32, true, true); else QN_GO(QN_F32, true, false); }
+                else { if (z) QN_GO(QN_F32, false, true); else QN_GO(QN_F32, false, false); }
+            } else if (dtype == QN_BF16) {
+                if (aligned) { if (z) QN_GO(QN_BF16, true, true); else QN_GO(QN_BF16, true, false); }
+                else { if (z) QN_GO(QN_BF16, false, true); else QN_GO(QN_BF16, false, false); }
+            } else {
+                if (aligned) { if (z) QN_GO(QN_F16, true, true); else QN_GO(QN_F16, true, false); }
+                else { if (z) QN_GO(QN_F16, false, true); else QN_GO(QN_F16, false, false); }
+            }
 #undef QN_GO
+        }
     }
     if (check_launch() != QN_OK) return QN_ELAUNCH;
     {
@@ -649,15 +753,16 @@ int launch_gram_raw(const void *grads, int dtype, int64_t n, int m, int64_t ld,
     raw->mraw = ws->mraw;
     raw->entries = entries;
     raw->z_mode = z != nullptr ? 1 : 0;
-    raw->pack = pack_for(m);
+    raw->pack = small ? 1 : gram_pack(m);
     return check_launch();
 }
 
 int launch_gram(const void *grads, int dtype, int64_t n, int m, int64_t ld,
-                Workspace *ws, const float *z, double *C, double *w, hipStream_t stream)
+                Workspace *ws, const float *z, double *C, double *w, hipStream_t stream,
+                int path)
 {
     RawGram raw;
-    const int rc = launch_gram_raw(grads, dtype, n, m, ld, ws, z, &raw, stream);
+    const int rc = launch_gram_raw(grads, dtype, n, m, ld, ws, z, &raw, stream, path);
     if (rc != QN_OK)
         return rc;
     TraceScope ts(QN_K_PROJECT, stream);

@@ -57,10 +57,28 @@ int launch_coef(const double *sigma, const double *V, const int *j, const double
     return check_launch();
 }
 
-static bool bad_args(const void *a, int dtype, int64_t n, int m, int64_t ld)
+int run_hinv(const void *thetas, const void *grads, int dtype, const float *z, int64_t n,
+             int m, int64_t ld, float lambda, float *out, int *j_out, Workspace *ws,
+             hipStream_t s)
 {
-    return a == nullptr || (dtype != QN_F32 && dtype != QN_BF16 && dtype != QN_F16) || n < 1 || m < 1 ||
-           m > QN_MAX_M || ld < n;
+    RawGram raw;
+    int rc = launch_gram_raw(grads, dtype, n, m, ld, ws, z, &raw, s);
+    if (rc != QN_OK)
+        return rc;
+    double *c64 = dtype == QN_F32 ? ws->cz64 : nullptr;
+    rc = launch_eig(nullptr, nullptr, m, lambda, nullptr, nullptr, ws->cz, j_out, s, &raw, c64);
+    if (rc != QN_OK)
+        return rc;
+    return launch_apply(thetas, grads, dtype, n, m, ld, ws->cz, z, 0.0f, nullptr, out,
+                        ws->cu_count, s, c64);
+}
+
+static bool bad_hinv_args(const void *thetas, const void *grads, int dtype, const float *z,
+                          int64_t n, int m, int64_t ld, float lambda, const float *out,
+                          const int *j_out)
+{
+    return bad_matrix_args(thetas, dtype, n, m, ld) || !grads || !z || !out || !j_out ||
+           !std::isfinite(lambda) || !(lambda > 0.0f);
 }
 
 }  // namespace qn
@@ -72,14 +90,31 @@ extern "C" {
 int qn_gemv_t_ex(const void *grads, int dtype, const float *z, int64_t n, int m,
                  int64_t ld, double *w, qn_stream_t stream)
 {
-    if (bad_args(grads, dtype, n, m, ld) || !z || !w)
+    if (bad_matrix_args(grads, dtype, n, m, ld) || !z || !w)
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    const int rc = get_workspace(&ws);
+    Workspace ws;
+    const int rc = get_lib_workspace(n, m, dtype, &ws);
     if (rc != QN_OK)
         return rc;
     // the Gram matrix of the same pass is not asked for here
-    return launch_gram(grads, dtype, n, m, ld, ws, z, ws->Ct, w, static_cast<hipStream_t>(stream));
+    return launch_gram(grads, dtype, n, m, ld, &ws, z, ws.Ct, w, static_cast<hipStream_t>(stream));
+}
+
+int qn_gemv_t_ws(const void *grads, int dtype, const float *z, int64_t n, int m,
+                 int64_t ld, double *w, void *workspace, size_t workspace_bytes,
+                 qn_stream_t stream)
+{
+    if (bad_matrix_args(grads, dtype, n, m, ld) || !z || !w)
+        return QN_EINVAL;
+    Device *d = nullptr;
+    int rc = get_device(&d);
+    if (rc != QN_OK)
+        return rc;
+    Workspace ws;
+    rc = carve_workspace(workspace, workspace_bytes, n, m, dtype, d->cu_count, &ws);
+    if (rc != QN_OK)
+        return rc;
+    return launch_gram(grads, dtype, n, m, ld, &ws, z, ws.Ct, w, static_cast<hipStream_t>(stream));
 }
 
 int qn_coef(const double *sigma, const double *V, const int *j, const double *w, int m,
@@ -87,8 +122,8 @@ int qn_coef(const double *sigma, const double *V, const int *j, const double *w,
 {
     if (!sigma || !V || !j || !w || !c || m < 1 || m > QN_MAX_M)
         return QN_EINVAL;
-    Workspace *ws = nullptr;   // arch check only
-    const int rc = get_workspace(&ws);
+    Device *d = nullptr;   // architecture check
+    const int rc = get_device(&d);
     if (rc != QN_OK)
         return rc;
     return launch_coef(sigma, V, j, w, m, c, static_cast<hipStream_t>(stream));
@@ -98,13 +133,13 @@ int qn_hinv_apply_ex(const void *thetas, const void *grads, int dtype, const flo
                      int64_t n, int m, int64_t ld, const float *c, float *out,
                      qn_stream_t stream)
 {
-    if (bad_args(thetas, dtype, n, m, ld) || !grads || !z || !c || !out)
+    if (bad_matrix_args(thetas, dtype, n, m, ld) || !grads || !z || !c || !out)
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    const int rc = get_workspace(&ws);
+    Device *d = nullptr;
+    const int rc = get_device(&d);
     if (rc != QN_OK)
         return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, c, z, 0.0f, nullptr, out, ws->cu_count,
+    return launch_apply(thetas, grads, dtype, n, m, ld, c, z, 0.0f, nullptr, out, d->cu_count,
                         static_cast<hipStream_t>(stream));
 }
 
@@ -112,23 +147,32 @@ int qn_hinv_ex(const void *thetas, const void *grads, int dtype, const float *z,
                int64_t n, int m, int64_t ld, float lambda, float *out, int *j_out,
                qn_stream_t stream)
 {
-    if (bad_args(thetas, dtype, n, m, ld) || !grads || !z || !out || !j_out ||
-        !std::isfinite(lambda) || !(lambda > 0.0f))
+    if (bad_hinv_args(thetas, grads, dtype, z, n, m, ld, lambda, out, j_out))
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    int rc = get_workspace(&ws);
+    Workspace ws;
+    const int rc = get_lib_workspace(n, m, dtype, &ws);
     if (rc != QN_OK)
         return rc;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    RawGram raw;
-    rc = launch_gram_raw(grads, dtype, n, m, ld, ws, z, &raw, s);
+    return run_hinv(thetas, grads, dtype, z, n, m, ld, lambda, out, j_out, &ws,
+                    static_cast<hipStream_t>(stream));
+}
+
+int qn_hinv_ws(const void *thetas, const void *grads, int dtype, const float *z,
+               int64_t n, int m, int64_t ld, float lambda, float *out, int *j_out,
+               void *workspace, size_t workspace_bytes, qn_stream_t stream)
+{
+    if (bad_hinv_args(thetas, grads, dtype, z, n, m, ld, lambda, out, j_out))
+        return QN_EINVAL;
+    Device *d = nullptr;
+    int rc = get_device(&d);
     if (rc != QN_OK)
         return rc;
-    rc = launch_eig(nullptr, nullptr, m, lambda, nullptr, nullptr, ws->cz, j_out, s, &raw);
+    Workspace ws;
+    rc = carve_workspace(workspace, workspace_bytes, n, m, dtype, d->cu_count, &ws);
     if (rc != QN_OK)
         return rc;
-    return launch_apply(thetas, grads, dtype, n, m, ld, ws->cz, z, 0.0f, nullptr, out,
-                        ws->cu_count, s);
+    return run_hinv(thetas, grads, dtype, z, n, m, ld, lambda, out, j_out, &ws,
+                    static_cast<hipStream_t>(stream));
 }
 
 int qn_hinv(const float *thetas, const float *grads, const float *z, int64_t n, int m,

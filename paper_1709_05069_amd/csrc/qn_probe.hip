@@ -56,13 +56,13 @@ int qn_probe_copy(const void *src, void *dst, int64_t bytes, qn_stream_t stream)
         reinterpret_cast<uintptr_t>(src) % 16 != 0 ||
         reinterpret_cast<uintptr_t>(dst) % 16 != 0)
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    const int rc = get_workspace(&ws);
+    Device *dev = nullptr;
+    const int rc = get_device(&dev);
     if (rc != QN_OK)
         return rc;
     const int64_t nvec = bytes / 16;
     int64_t want = (nvec + kProbeThreads - 1) / kProbeThreads;
-    const int64_t cap = static_cast<int64_t>(ws->cu_count) * 8;
+    const int64_t cap = static_cast<int64_t>(dev->cu_count) * 8;
     const int grid = static_cast<int>(want < cap ? want : cap);
     hipLaunchKernelGGL(probe_copy, dim3(grid), dim3(kProbeThreads), 0,
                        static_cast<hipStream_t>(stream),
@@ -75,12 +75,12 @@ int qn_probe_read(const void *src, int64_t bytes, float *sink, qn_stream_t strea
     if (!src || !sink || bytes < 16 || bytes % 16 != 0 ||
         reinterpret_cast<uintptr_t>(src) % 16 != 0)
         return QN_EINVAL;
-    Workspace *ws = nullptr;
-    const int rc = get_workspace(&ws);
+    Device *dev = nullptr;
+    const int rc = get_device(&dev);
     if (rc != QN_OK)
         return rc;
     const int64_t nvec = bytes / 16;
-    const int grid = ws->cu_count * 2;   // sink holds qn_probe_sink_floats() >= grid*256 floats
+    const int grid = dev->cu_count * 2;   // sink holds qn_probe_sink_floats() >= grid*256 floats
     hipLaunchKernelGGL(probe_read, dim3(grid), dim3(kProbeThreads), 0,
                        static_cast<hipStream_t>(stream),
                        static_cast<const v4f *>(src), nvec, sink);
@@ -89,10 +89,10 @@ int qn_probe_read(const void *src, int64_t bytes, float *sink, qn_stream_t strea
 
 int qn_probe_sink_floats(void)
 {
-    Workspace *ws = nullptr;
-    if (get_workspace(&ws) != QN_OK)
+    Device *dev = nullptr;
+    if (get_device(&dev) != QN_OK)
         return -1;
-    return ws->cu_count * 8 * kProbeThreads;
+    return dev->cu_count * 8 * kProbeThreads;
 }
 
 }  // extern "C"

@@ -58,12 +58,51 @@ def _dev_out(t, shape, dtype, device, name):
     return t
 
 
+# Scratch memory of the library's passes: torch allocates it, one buffer per
+# (device, stream) sized for the largest problem (a few MB), kept for the life of
+# the process, and every call goes through the library's *_ws entry points, so the
+# library itself allocates nothing.  Calls on different streams use different
+# buffers and may overlap.
+_WORKSPACES = {}
+_MAX_ROWS = 1 << 40
+
+
+def workspace_bytes(n: int, m: int, dtype: int = QN_F32) -> int:
+    """Bytes of scratch memory an (n, m) problem of this element type needs."""
+    return int(_lib.load().qn_workspace_bytes(int(n), int(m), int(dtype)))
+
+
+def _workspace(device, stream, workspace=None):
+    """(pointer, bytes) of the scratch buffer for a call on this device and stream."""
+    if workspace is not None:
+        if not (workspace.is_cuda and workspace.dtype == torch.uint8
+                and workspace.is_contiguous() and workspace.device == device):
+            raise QnError("workspace must be a contiguous uint8 tensor on the inputs' device")
+        return workspace.data_ptr(), workspace.numel()
+    s = torch.cuda.current_stream(device) if stream is None else stream
+    key = (device.index, s.cuda_stream)
+    buf = _WORKSPACES.get(key)
+    if buf is None:
+        with torch.cuda.device(device):
+            need = max(workspace_bytes(_MAX_ROWS, 64, dt) for dt in (QN_F32, QN_BF16, QN_F16))
+        if need == 0:
+            raise QnError("qn_workspace_bytes failed")
+        buf = torch.empty(need, dtype=torch.uint8, device=device)
+        _WORKSPACES[key] = buf
+    return buf.data_ptr(), buf.numel()
+
+
 def qn_init():
-    _check(_lib.load().qn_init(), "qn_init")
+    """Prepares the current device and this stream's scratch buffer ahead of the
+    first call (nothing is allocated inside the calls after it)."""
+    dev = torch.device("cuda", torch.cuda.current_device())
+    _workspace(dev, None)
 
 
-def qn_update(thetas, grads, tau, lam, theta_new=None, j_out=None, stream=None):
-    """theta_new (n fp32) and j_out (1 int32, on device) for the whole step."""
+def qn_update(thetas, grads, tau, lam, theta_new=None, j_out=None, stream=None,
+              workspace=None):
+    """theta_new (n fp32) and j_out (1 int32, on device) for the whole step.
+    workspace: optional uint8 device tensor of at least workspace_bytes(n, m, dtype)."""
     L = _lib.load()
     dt, m, n, ld = _worker(thetas, "thetas")
     dg, mg, ng, ldg = _worker(grads, "grads")
@@ -71,20 +110,42 @@ def qn_update(thetas, grads, tau, lam, theta_new=None, j_out=None, stream=None):
         raise QnError("thetas and grads must agree in dtype, shape and stride")
     theta_new = _dev_out(theta_new, (n,), torch.float32, thetas.device, "theta_new")
     j_out = _dev_out(j_out, (1,), torch.int32, thetas.device, "j_out")
-    _check(L.qn_update_ex(thetas.data_ptr(), grads.data_ptr(), dt, n, m, ld,
+    ws, ws_bytes = _workspace(thetas.device, stream, workspace)
+    _check(L.qn_update_ws(thetas.data_ptr(), grads.data_ptr(), dt, n, m, ld,
                           float(tau), float(lam), theta_new.data_ptr(),
-                          j_out.data_ptr(), _stream(stream)), "qn_update")
+                          j_out.data_ptr(), ws, ws_bytes, _stream(stream)), "qn_update")
     return theta_new, j_out
 
 
-def qn_gram(grads, C=None, w=None, stream=None):
+def qn_gram(grads, C=None, w=None, stream=None, workspace=None):
     """C = G^T G (m, m) and w = G^T g_bar (m,), float64 on device."""
     L = _lib.load()
     dt, m, n, ld = _worker(grads, "grads")
     C = _dev_out(C, (m, m), torch.float64, grads.device, "C")
     w = _dev_out(w, (m,), torch.float64, grads.device, "w")
-    _check(L.qn_gram_ex(grads.data_ptr(), dt, n, m, ld, C.data_ptr(),
-                        w.data_ptr(), _stream(stream)), "qn_gram")
+    ws, ws_bytes = _workspace(grads.device, stream, workspace)
+    _check(L.qn_gram_ws(grads.data_ptr(), dt, n, m, ld, C.data_ptr(),
+                        w.data_ptr(), ws, ws_bytes, _stream(stream)), "qn_gram")
+    return C, w
+
+
+GRAM_AUTO, GRAM_STREAM, GRAM_SMALL = 0, 1, 2
+
+
+def diag_gram(grads, path, z=None, stream=None):
+    """qn_gram with the stage-1 kernel named by the caller (diagnostics): the
+    matrix-core streaming pass (GRAM_STREAM) or the fp64 vector kernel
+    (GRAM_SMALL).  With z (n fp32 values) w = G^T z.  Uses the library's own
+    workspace."""
+    L = _lib.load()
+    dt, m, n, ld = _worker(grads, "grads")
+    if z is not None:
+        _vector(z, n, grads.device, "z")
+    C = torch.empty((m, m), dtype=torch.float64, device=grads.device)
+    w = torch.empty(m, dtype=torch.float64, device=grads.device)
+    _check(L.qn_diag_gram_ex(grads.data_ptr(), dt, z.data_ptr() if z is not None else None,
+                             n, m, ld, int(path), C.data_ptr(), w.data_ptr(),
+                             _stream(stream)), "qn_diag_gram")
     return C, w
 
 
@@ -138,8 +199,9 @@ def qn_hinv(thetas, grads, z, lam, out=None, j_out=None, stream=None):
     _vector(z, n, thetas.device, "z")
     out = _dev_out(out, (n,), torch.float32, thetas.device, "out")
     j_out = _dev_out(j_out, (1,), torch.int32, thetas.device, "j_out")
-    _check(L.qn_hinv_ex(thetas.data_ptr(), grads.data_ptr(), dt, z.data_ptr(), n, m,
-                        ld, float(lam), out.data_ptr(), j_out.data_ptr(),
+    ws, ws_bytes = _workspace(thetas.device, stream)
+    _check(L.qn_hinv_ws(thetas.data_ptr(), grads.data_ptr(), dt, z.data_ptr(), n, m,
+                        ld, float(lam), out.data_ptr(), j_out.data_ptr(), ws, ws_bytes,
                         _stream(stream)), "qn_hinv")
     return out, j_out
 
@@ -150,8 +212,9 @@ def qn_gemv_t(grads, z, stream=None):
     dt, m, n, ld = _worker(grads, "grads")
     _vector(z, n, grads.device, "z")
     w = torch.empty(m, dtype=torch.float64, device=grads.device)
-    _check(L.qn_gemv_t_ex(grads.data_ptr(), dt, z.data_ptr(), n, m, ld, w.data_ptr(),
-                          _stream(stream)), "qn_gemv_t")
+    ws, ws_bytes = _workspace(grads.device, stream)
+    _check(L.qn_gemv_t_ws(grads.data_ptr(), dt, z.data_ptr(), n, m, ld, w.data_ptr(),
+                          ws, ws_bytes, _stream(stream)), "qn_gemv_t")
     return w
 
 
@@ -202,10 +265,11 @@ def qn_update_bounded(thetas, grads, tau, lam, mode, theta_new=None, j_out=None,
     theta_new = _dev_out(theta_new, (n,), torch.float32, thetas.device, "theta_new")
     j_out = _dev_out(j_out, (1,), torch.int32, thetas.device, "j_out")
     tau_out = _dev_out(tau_out, (1,), torch.float32, thetas.device, "tau_out")
-    _check(L.qn_update_bounded_ex(thetas.data_ptr(), grads.data_ptr(), dt, n, m, ld,
+    ws, ws_bytes = _workspace(thetas.device, stream)
+    _check(L.qn_update_bounded_ws(thetas.data_ptr(), grads.data_ptr(), dt, n, m, ld,
                                   float(tau), float(lam), int(mode),
                                   theta_new.data_ptr(), j_out.data_ptr(),
-                                  tau_out.data_ptr(), _stream(stream)),
+                                  tau_out.data_ptr(), ws, ws_bytes, _stream(stream)),
            "qn_update_bounded")
     return theta_new, j_out, tau_out
 

@@ -10,6 +10,7 @@ import torch
 import oracle
 import paper_1709_05069_amd as qn
 from paper_1709_05069_amd import synth
+from parity_util import assert_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -65,7 +66,7 @@ def test_update_bounded_matches_oracle(name, n, m, mode):
             assert abs(float(td.item()) - t_eff) <= 1e-5 * t_eff
         else:
             assert float(td.item()) == tau32          # untouched, bit for bit
-        assert rel(out.cpu().numpy(), want) <= tol
+        assert_close(out.cpu().numpy(), want, tol)
         if capped:   # the step theta_new - theta_bar on its own (resolvable in fp32 here)
             tb = oracle.row_means(th_np)
             assert rel(out.cpu().numpy().astype(np.float64) - tb, want - tb) <= 1e-3

@@ -1,0 +1,109 @@
+"""The two stage-1 kernels of the Gram pass, each forced on the same inputs:
+the matrix-core streaming pass and the fp64 vector kernel that problems of up to
+16384 rows take.  Both against the oracle; then the whole step where n is of the
+order of m or below, which is what the fp64 kernel is there for."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1709_05069_amd as qn
+from paper_1709_05069_amd import synth
+from parity_util import rel, assert_close, step_tolerance
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+CASES = [
+    ("tiny_exact", 1, 2), ("tiny_exact", 1, 64), ("tiny_exact", 2, 3), ("tiny_exact", 63, 64),
+    ("tiny_exact", 64, 64), ("tiny_exact", 65, 33), ("small_mlp", 127, 15), ("small_mlp", 777, 3),
+    ("small_mlp", 4096, 4), ("gpt2_small", 129, 32), ("gpt2_small", 5000, 8),
+    ("gpt2_small", 16384, 32), ("gpt2_small", 16385, 32), ("resnet50", 20001, 48),
+    ("stress_1b_bf16", 4097, 8), ("stress_1b_bf16", 100, 64), ("stress_1b_bf16", 12345, 23),
+    ("gpt2_small", 40000, 64), ("gpt2_small", 30001, 5),
+]
+
+
+def _f16(wl):
+    from dataclasses import replace
+    return replace(wl, storage="f16")
+
+
+@pytest.mark.parametrize("name,n,m", CASES)
+@pytest.mark.parametrize("f16", [False, True])
+def test_both_gram_kernels_match_the_oracle(name, n, m, f16):
+    from dataclasses import replace
+    wl = replace(synth.WORKLOADS[name].scaled(n), m=m)
+    if f16:
+        if wl.storage != "f32" or n % 3 == 0:
+            pytest.skip("binary16 is drawn for part of the fp32 cases")
+        wl = _f16(wl)
+    th, gr = synth.make_worker_states(wl, DEV)
+    gr_np = synth.to_numpy_stored(gr)
+    Co, wo = oracle.gram_accumulate(gr_np)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(n + m)
+    z = torch.randn(n, device=DEV, generator=gen)
+    gb = oracle.row_means(gr_np)
+    wz = oracle.gemv_t(oracle.centre(gr_np, gb), z.cpu().numpy().astype(np.float64))
+    for path, tol in ((qn.GRAM_SMALL, 1e-13), (qn.GRAM_STREAM, 1e-5)):
+        C, w = qn.diag_gram(gr, path)
+        Cz, wzg = qn.diag_gram(gr, path, z=z)
+        C, w, Cz, wzg = (t.cpu().numpy() for t in (C, w, Cz, wzg))
+        if m == 1:
+            assert np.all(C == 0) and np.all(w == 0) and np.all(wzg == 0)
+            continue
+        assert rel(C, Co) <= tol and rel(w, wo) <= tol, (path, rel(C, Co), rel(w, wo))
+        assert np.array_equal(C, C.T)
+        assert rel(Cz, Co) <= tol
+        # z is a random vector: G^T z is small against ||G|| ||z||, so measure it there
+        scale = np.sqrt(np.trace(Co)) * np.linalg.norm(z.cpu().numpy())
+        assert np.linalg.norm(wzg - wz) <= max(tol, 1e-6 if path == qn.GRAM_STREAM else tol) * scale
+    # what qn_gram itself runs is one of the two, by n
+    C, w = qn.qn_gram(gr)
+    Cf, wf = qn.diag_gram(gr, qn.GRAM_SMALL if n <= 16384 else qn.GRAM_STREAM)
+    assert torch.equal(C, Cf) and torch.equal(w, wf)
+
+
+# n of the order of m and below: g_bar lies (almost) inside span{u_k}, so G c
+# cancels g_bar in eq. (4) and theta_new is far smaller than its terms.
+SMALL_N = [(64, 1, 0.3), (63, 64, 0.01), (63, 63, 0.01), (9, 18, 0.05), (64, 2, 0.01), (32, 8, 0.05),
+           (16, 16, 0.05), (8, 100, 0.05), (33, 40, 0.01), (64, 200, 0.01), (4, 3, 0.05),
+           (2, 1, 0.3), (48, 47, 0.3), (17, 16, 0.01)]
+
+
+@pytest.mark.parametrize("m,n,lam", SMALL_N)
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_whole_step_with_n_of_the_order_of_m(m, n, lam, seed):
+    rng = np.random.default_rng(50 * m + n + 1000 * seed)
+    a = np.exp(1.5 * rng.standard_normal(n)).astype(np.float32)
+    b = rng.standard_normal(n).astype(np.float32)
+    th_np = (rng.standard_normal(n)[None, :] + 0.01 * rng.standard_normal((m, n))).astype(np.float32)
+    gr_np = (a[None, :] * th_np - b[None, :]
+             + (0.01 * rng.standard_normal((m, n))).astype(np.float32)).astype(np.float32)
+    tau = 1.0
+    lam32 = np.float32(lam)
+    lit = oracle.update_literal(th_np, gr_np, tau, lam32)       # eq. (4) with explicit u_k, y_k
+    ref = oracle.update_streaming(th_np, gr_np, tau, lam32)     # closed form: also c and w
+    assert lit["j"] == ref["j"]
+    assert rel(ref["theta_new"], lit["theta_new"]) <= 1e-9
+    ref["theta_new"] = lit["theta_new"]
+    sig = ref["sigma"]
+    rank = min(m - 1, n)
+    if np.min(np.abs(sig[:rank] / sig[0] - lam32)) < 1e-4:
+        pytest.skip("a singular value sits at the cutoff: j is not well posed")
+    th, gr = torch.tensor(th_np, device=DEV), torch.tensor(gr_np, device=DEV)
+    out, j = qn.qn_update(th, gr, tau, lam)
+    assert int(j.item()) == ref["j"]
+    tol = step_tolerance(ref, th_np, gr_np, tau, 4e-6)
+    assert tol <= 1e-5, "the documented bound itself stays inside the contract here"
+    assert_close(out.cpu().numpy(), ref["theta_new"], tol, k=4.0,
+                 what=f"m={m} n={n} lam={lam} seed={seed}")
+    # the operator on a random vector, against the literal eq. (4)
+    z = rng.standard_normal(n).astype(np.float32)
+    h, jh = qn.qn_hinv(th, gr, torch.tensor(z, device=DEV), lam)
+    tb, gb = oracle.row_means(th_np), oracle.row_means(gr_np)
+    href = oracle.apply_Hinv_literal(oracle.centre(th_np, tb), oracle.centre(gr_np, gb),
+                                     ref["sigma"], ref["V"], ref["j"], z.astype(np.float64))
+    assert int(jh.item()) == ref["j"]
+    assert rel(h.cpu().numpy(), href) <= 1e-5

@@ -3,7 +3,8 @@ element by element on the same seeded inputs.
 
 Tolerances:
   j                       exact
-  theta_new               relative L2 <= 1e-5 (fp32 storage), <= 1e-3 (bf16 storage)
+  theta_new               relative L2 <= 1e-5 (fp32 storage), <= 1e-3 (bf16 storage),
+                          and element by element |got - want| <= 2 tol max|want|
 internal, stricter than the headline needs:
   C, w                    Frobenius / L2 relative <= 1e-5
   c                       relative L2 <= 1e-4
@@ -16,17 +17,10 @@ import torch
 import oracle
 import paper_1709_05069_amd as qn
 from paper_1709_05069_amd import synth
+from parity_util import rel, assert_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-
-
-def rel(a, b):
-    a = np.asarray(a, np.float64)
-    b = np.asarray(b, np.float64)
-    d = np.linalg.norm(a - b)
-    s = np.linalg.norm(b)
-    return d / s if s > 0 else d
 
 
 def gen(name, n, m=None):
@@ -190,7 +184,7 @@ def test_apply_matches_oracle(name, n, m):
     out = qn.qn_apply(th, gr, torch.tensor(c, device=DEV), wl.tau)
     torch.cuda.synchronize()
     ref = oracle.apply_closed_form(th_np, gr_np, c.astype(np.float64), wl.tau)
-    assert rel(out.cpu().numpy(), ref) <= 2e-6
+    assert_close(out.cpu().numpy(), ref, 2e-6, k=4.0)
     # the correction alone (difference to the SGD form) is also right
     sgd = oracle.apply_closed_form(th_np, gr_np, np.zeros(m), wl.tau)
     if m > 1:
@@ -206,10 +200,10 @@ def test_apply_shards_and_unaligned():
     cd = torch.tensor(c, device=DEV)
     ref = oracle.apply_closed_form(th_np, gr_np, c.astype(np.float64), 0.7)
     out = qn.qn_apply(th, gr, cd, 0.7)                   # odd n: element-wise path
-    assert rel(out.cpu().numpy(), ref) <= 2e-6
+    assert_close(out.cpu().numpy(), ref, 2e-6, k=4.0)
     for r0, rows in ((3, 30000), (4, 1025), (16, 16)):
         o = qn.qn_apply(th[:, r0:r0 + rows], gr[:, r0:r0 + rows], cd, 0.7)
-        assert rel(o.cpu().numpy(), ref[r0:r0 + rows]) <= 2e-6
+        assert_close(o.cpu().numpy(), ref[r0:r0 + rows], 2e-6, k=4.0)
 
 
 # ----------------------------------------------------------- whole step ----
@@ -232,7 +226,7 @@ def test_update_matches_oracle(name, n, m):
     out = out.cpu().numpy()
     assert int(j.item()) == ref["j"] == wl.m - 1
     tol = 1e-5 if wl.storage == "f32" else 1e-3
-    assert rel(out, ref["theta_new"]) <= tol
+    assert_close(out, ref["theta_new"], tol)
     # internal parity of the pieces
     C, w = qn.qn_gram(gr)
     sigma, V, c, j2 = qn.qn_eig(C, w, wl.lam)
@@ -242,9 +236,14 @@ def test_update_matches_oracle(name, n, m):
     assert rel(c.cpu().numpy(), ref["c"]) <= 1e-4
     sgd = oracle.apply_closed_form(th_np, gr_np, np.zeros(wl.m), wl.tau)
     assert rel(out.astype(np.float64) - sgd, ref["theta_new"] - sgd) <= 1e-4
-    # composing the three entry points gives the same bits as qn_update
+    # composing the three entry points gives the fused step: the same bits with
+    # 16-bit storage; with fp32 storage qn_update hands the apply pass c in double
+    # where the pieces pass its fp32 rounding, so to fp32 rounding of the result
     out2 = qn.qn_apply(th, gr, c, wl.tau)
-    assert torch.equal(out2.cpu(), torch.from_numpy(out))
+    if wl.storage == "f32":
+        assert_close(out2.cpu().numpy(), out, 2e-7, k=8.0)
+    else:
+        assert torch.equal(out2.cpu(), torch.from_numpy(out))
 
 
 def test_update_is_bitwise_reproducible():
@@ -307,7 +306,7 @@ def test_cutoff_below_full_rank_on_engineered_workers():
         out, j = qn.qn_update(torch.tensor(thetas, device=DEV),
                               torch.tensor(grads, device=DEV), tau, lam)
         assert int(j.item()) == ref["j"]
-        assert rel(out.cpu().numpy(), ref["theta_new"]) <= 1e-5
+        assert_close(out.cpu().numpy(), ref["theta_new"], 1e-5)
 
 
 # ------------------------------------------------ harder inputs, fused path ----
@@ -340,7 +339,7 @@ def test_update_cutoff_inside_the_fused_step(m, lam, expect_j):
     th, gr = torch.tensor(thetas, device=DEV), torch.tensor(grads, device=DEV)
     out, j = qn.qn_update(th, gr, 0.8, lam)
     assert int(j.item()) == expect_j
-    assert rel(out.cpu().numpy(), ref["theta_new"]) <= 1e-5
+    assert_close(out.cpu().numpy(), ref["theta_new"], 1e-5)
     # the step on its own; the coefficient along v_k carries ~1e-7 (sigma_1/sigma_k)^2
     tb = oracle.row_means(thetas)
     amp = (ref["sigma"][0] / ref["sigma"][expect_j - 1]) ** 2
@@ -362,7 +361,7 @@ def test_update_with_large_common_gradient_and_extreme_scales(g_offset, g_scale)
     assert rel(C.cpu().numpy(), ref["C"]) <= 1e-5 and rel(w.cpu().numpy(), ref["w"]) <= 1e-5
     out, j = qn.qn_update(th, gr, 1e-3 / g_scale, 0.05)
     assert int(j.item()) == m - 1
-    assert rel(out.cpu().numpy(), ref["theta_new"]) <= 1e-5
+    assert_close(out.cpu().numpy(), ref["theta_new"], 1e-5)
 
 
 def test_gradient_magnitudes_outside_the_fp32_range_of_their_squares():

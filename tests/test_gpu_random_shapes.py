@@ -1,25 +1,22 @@
-"""Seeded random shapes: m, n, storage type (fp32, bf16, fp16), leading dimension and base-pointer
-offset drawn at random (ragged tiles, every alignment, row shards of a wider
-matrix), each compared with the oracle: Gram, whole step and the operator on a
-random vector."""
+"""Seeded random shapes: m, n (from 1 upward, so also n < m, where g_bar lies
+inside span{u_k} and G c cancels it), storage type (fp32, bf16, fp16), leading
+dimension and base-pointer offset drawn at random (ragged tiles, every alignment,
+row shards of a wider matrix), each compared with the oracle: Gram, whole step
+and the operator on a random vector.  The tolerance of the whole step is the one
+the header documents, computed from the oracle's own quantities."""
 import numpy as np
 import pytest
 import torch
 
 import oracle
 import paper_1709_05069_amd as qn
+from parity_util import rel, step_tolerance
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 M_CHOICES = [1, 2, 3, 4, 5, 7, 8, 9, 12, 16, 17, 24, 31, 32, 33, 40, 48, 49, 63, 64]
-N_EDGES = [255, 256, 257, 511, 513, 1023, 1025, 2047, 2049, 4095, 4097, 8193]
-
-
-def rel(a, b):
-    a = np.asarray(a, np.float64)
-    b = np.asarray(b, np.float64)
-    nb = np.linalg.norm(b)
-    return np.linalg.norm(a - b) / (nb if nb > 0 else 1.0)
+N_EDGES = [1, 2, 3, 63, 64, 65, 255, 256, 257, 511, 513, 1023, 1025, 2047, 2049, 4095, 4097,
+           8193, 16383, 16384, 16385, 16897]
 
 
 def stored(t):
@@ -27,16 +24,20 @@ def stored(t):
     return t.view(torch.uint16).cpu().numpy() if t.dtype == torch.bfloat16 else t.cpu().numpy()
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(8))
 def test_random_shapes_match_the_oracle(seed):
     rng = np.random.default_rng(1000 + seed)
     gen = torch.Generator(device=DEV)
     gen.manual_seed(seed)
-    for case in range(12):
+    for case in range(14):
         m = int(rng.choice(M_CHOICES))
-        # n well above m: with n ~ m the step is ill conditioned (see the operator tests)
-        n = int(rng.choice(N_EDGES)) if rng.random() < 0.4 else int(rng.integers(100 * m, 100 * m + 30_000))
-        n = max(n, 100 * m)
+        u = rng.random()
+        if u < 0.3:
+            n = int(rng.choice(N_EDGES))
+        elif u < 0.55:
+            n = int(rng.integers(1, 3 * m + 2))            # n of the order of m and below
+        else:
+            n = int(rng.integers(1, 60_000))
         kind = str(rng.choice(["f32", "f32", "bf16", "f16"]))
         bf = kind != "f32"
         ld = n + int(rng.integers(0, 9))
@@ -65,16 +66,22 @@ def test_random_shapes_match_the_oracle(seed):
             assert torch.all(C == 0) and torch.all(w == 0), tag
         ref = oracle.update_streaming(th_np, gr_np, tau, np.float32(lam))
         sig = ref["sigma"]
-        margin = np.min(np.abs(sig[:max(m - 1, 1)] / sig[0] - np.float32(lam))) if sig[0] > 0 else 1.0
+        # "same j" is well posed when no singular value sits at the cutoff; with
+        # n < m - 1 the trailing ones are rounding noise of either side
+        rank = min(m - 1, n)
+        margin = (np.min(np.abs(sig[:max(rank, 1)] / sig[0] - np.float32(lam)))
+                  if sig[0] > 0 else 1.0)
+        noise_ok = sig[0] == 0 or rank >= m - 1 or sig[rank] < 1e-3 * np.float32(lam) * sig[0]
         out, j = qn.qn_update(th, gr, tau, lam)
         z = rnd(n)
         h, jh = qn.qn_hinv(th, gr, z, lam)
-        if margin > 1e-5:                     # else "same j" is not well posed
+        if margin > 1e-5 and noise_ok:
             assert int(j.item()) == ref["j"] and int(jh.item()) == ref["j"], tag
-            tol = 1e-3 if bf else 1e-5
-            assert rel(out.cpu().numpy(), ref["theta_new"]) <= tol, tag
+            base = 1e-3 if bf else 1e-5
+            tol = step_tolerance(ref, th_np, gr_np, tau, base)
+            assert rel(out.cpu().numpy(), ref["theta_new"]) <= tol, (tag, tol)
             tb, gb = oracle.row_means(th_np), oracle.row_means(gr_np)
             href = oracle.apply_Hinv_literal(oracle.centre(th_np, tb), oracle.centre(gr_np, gb),
                                              ref["sigma"], ref["V"], ref["j"],
                                              z.cpu().numpy().astype(np.float64))
-            assert rel(h.cpu().numpy(), href) <= max(tol, 1e-4), tag
+            assert rel(h.cpu().numpy(), href) <= max(base, 1e-4), tag
