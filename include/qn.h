@@ -200,6 +200,25 @@ int qn_update_ws(const void *thetas, const void *grads, int dtype, int64_t n, in
 int qn_gram_ws(const void *grads, int dtype, int64_t n, int m, int64_t ld, double *C,
                double *w, void *workspace, size_t workspace_bytes, qn_stream_t stream);
 
+/* ---- the whole step for callers that cannot allocate -------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid
+ * hipMalloc: qn_update_ex with its scratch memory in a static device array inside
+ * the library (6 MiB, held by every device the library runs on until the process
+ * ends) instead of an allocated or caller-owned workspace.  The call allocates
+ * and frees nothing, also on its first use on a device (which looks up the
+ * array's address and sets kernel attributes; qn_init() does the same ahead of
+ * time).  Same kernels, same results bit for bit as qn_update_ex.
+ * Limit: qn_workspace_bytes(n, m, dtype) must not exceed 6 MiB, else
+ * QN_EWORKSPACE and nothing is enqueued (it is at most about 5.6 MB for every
+ * n and m <= QN_MAX_M on a device of up to 256 compute units).
+ * All calls on one device share that device's array, which keeps the last call's
+ * contents; nothing in it needs clearing between calls.  Calls that may overlap
+ * in time on one device (different streams or host threads) race: serialise
+ * them, or use qn_update_ws. */
+int qn_update_noalloc(const void *thetas, const void *grads, int dtype, int64_t n, int m,
+                      int64_t ld, float tau, float lambda, float *theta_new, int *j_out,
+                      qn_stream_t stream);
+
 /* ---- the operator of eq. (3)/(4) on an arbitrary vector ---------------------
  *   out = Hinv z = z_perp + sum_{k<=j} alpha_k sigma_k^-1 y_k,  alpha_k = z^T u_k,
  * identity on span{u_1..u_j}^perp and the secant inverse (G v_k -> Theta v_k) on

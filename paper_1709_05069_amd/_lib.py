@@ -17,6 +17,8 @@ SIGNATURES = {
     "qn_workspace_bytes": (_sz, [_i64, _int, _int]),
     "qn_update_ws": (_int, [_vp, _vp, _int, _i64, _int, _i64, _f32, _f32, _vp, _vp,
                             _vp, _sz, _vp]),
+    "qn_update_noalloc": (_int, [_vp, _vp, _int, _i64, _int, _i64, _f32, _f32, _vp, _vp,
+                                 _vp]),
     "qn_gram_ws": (_int, [_vp, _int, _i64, _int, _i64, _vp, _vp, _vp, _sz, _vp]),
     "qn_hinv_ws": (_int, [_vp, _vp, _int, _vp, _i64, _int, _i64, _f32, _vp, _vp,
                           _vp, _sz, _vp]),

@@ -11,6 +11,17 @@
 
 namespace qn {
 
+// ---------------------------------------------------------- static scratch --
+// Scratch memory of qn_update_noalloc: a device array inside the library's code
+// object, so that the entry point needs neither hipMalloc nor a workspace argument.
+// Every device the library runs on holds its own copy, at its own address, until
+// the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: get_device() looks the address up once per device and the
+// kernels are handed that pointer, never the name.  workspace_need() stays below
+// this size for every problem on a device of up to 256 compute units.
+constexpr size_t kStaticScratchBytes = 6u * 1024u * 1024u;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 // ------------------------------------------------------------- device state --
 constexpr int kMaxDevices = 64;
 static Device g_dev[kMaxDevices];
@@ -34,6 +45,13 @@ int get_device(Device **out)
             return QN_ELAUNCH;
         Device d{};
         d.cu_count = prop.multiProcessorCount;
+        // this device's copy of the static scratch array (the current device is `dev`)
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return QN_ELAUNCH;
+        }
+        d.static_scratch = ptr;
         g_dev[dev] = d;
         g_dev_ready[dev] = true;
     }
@@ -333,6 +351,30 @@ int qn_update_ws(const void *thetas, const void *grads, int dtype, int64_t n, in
     const int rc = get_caller_workspace(workspace, workspace_bytes, n, m, dtype, &ws);
     if (rc != QN_OK)
         return rc;
+    return run_update(thetas, grads, dtype, n, m, ld, tau, lambda, theta_new, j_out, &ws,
+                      static_cast<hipStream_t>(stream));
+}
+
+int qn_update_noalloc(const void *thetas, const void *grads, int dtype, int64_t n, int m,
+                      int64_t ld, float tau, float lambda, float *theta_new, int *j_out,
+                      qn_stream_t stream)
+{
+    if (bad_update_args(thetas, grads, dtype, n, m, ld, tau, lambda, theta_new, j_out))
+        return QN_EINVAL;
+    Device *d = nullptr;
+    int rc = get_device(&d);        // set-up only: no allocation
+    if (rc != QN_OK)
+        return rc;
+    // the problem's scratch must fit the static array
+    if (workspace_need(n, m, dtype, d->cu_count) > kStaticScratchBytes)
+        return QN_EWORKSPACE;
+    Workspace ws;
+    rc = carve_workspace(d->static_scratch, kStaticScratchBytes, n, m, dtype, d->cu_count, &ws);
+    if (rc != QN_OK)
+        return rc;
+    // Nothing in the scratch has to start at zero: every block of the Gram pass
+    // writes its whole partial, the reduction reads exactly the partials of this
+    // launch, and the eigen kernel writes c before the apply pass reads it.
     return run_update(thetas, grads, dtype, n, m, ld, tau, lambda, theta_new, j_out, &ws,
                       static_cast<hipStream_t>(stream));
 }

@@ -12,8 +12,9 @@
 namespace qn {
 
 // ---- workspace: a view into scratch memory that somebody else owns ------------
-// Carved from a caller's buffer (the *_ws entry points) or from the buffer the
-// library allocates once per device (the plain entry points).
+// Carved from a caller's buffer (the *_ws entry points), from the buffer the
+// library allocates once per device (the plain entry points) or from the static
+// device array (qn_update_noalloc).
 struct Workspace {
     double *partials;   // max_partials * gram_entries(m)
     int max_partials;   // blocks whose partial fits
@@ -44,9 +45,11 @@ struct Device {
     int cu_count;
     void *lib_ws;           // allocated by the plain entry points on first use, else null
     size_t lib_ws_bytes;
+    void *static_scratch;   // this device's copy of the static scratch array (its device address)
 };
-// The current device's state; on first use checks the architecture and opts the
-// kernels into their dynamic LDS sizes.  Allocates nothing.
+// The current device's state; on first use checks the architecture, opts the
+// kernels into their dynamic LDS sizes and looks up the address of the device's
+// copy of the static scratch array.  Allocates nothing.
 int get_device(Device **out);
 // The library-owned workspace of the plain entry points (hipMalloc on first use).
 int get_lib_workspace(int64_t n, int m, int dtype, Workspace *ws);

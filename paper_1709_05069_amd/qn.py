@@ -117,6 +117,22 @@ def qn_update(thetas, grads, tau, lam, theta_new=None, j_out=None, stream=None,
     return theta_new, j_out
 
 
+def qn_update_noalloc(thetas, grads, tau, lam, theta_new, j_out, stream=None):
+    """The whole step through the entry point that allocates nothing: its scratch
+    memory is a static device array inside the library.  The caller passes the
+    outputs (theta_new: n fp32, j_out: 1 int32)."""
+    L = _lib.load()
+    dt, m, n, ld = _worker(thetas, "thetas")
+    if (dt, m, n, ld) != _worker(grads, "grads"):
+        raise QnError("thetas and grads must agree in dtype, shape and stride")
+    theta_new = _dev_out(theta_new, (n,), torch.float32, thetas.device, "theta_new")
+    j_out = _dev_out(j_out, (1,), torch.int32, thetas.device, "j_out")
+    _check(L.qn_update_noalloc(thetas.data_ptr(), grads.data_ptr(), dt, n, m, ld,
+                               float(tau), float(lam), theta_new.data_ptr(),
+                               j_out.data_ptr(), _stream(stream)), "qn_update_noalloc")
+    return theta_new, j_out
+
+
 def qn_gram(grads, C=None, w=None, stream=None, workspace=None):
     """C = G^T G (m, m) and w = G^T g_bar (m,), float64 on device."""
     L = _lib.load()
