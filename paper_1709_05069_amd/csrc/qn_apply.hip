@@ -359,8 +359,7 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
         __syncthreads();
         // the slab's results are contiguous in memory: rows [base*R, (base+slab)*R)
         v4f_elem *dst = reinterpret_cast<v4f_elem *>(out) + base * Q;
-        const int64_t left = (nvec - base) * Q;
-        const int count = static_cast<int>(left < slab * Q ? left : slab * Q);
+        const int count = static_cast<int>(staged_slab_count(nvec, base, slab) * Q);
 #pragma unroll 1
         for (int i = threadIdx.x; i < count; i += kStagedThreads)
             __builtin_nontemporal_store(stage[i], dst + i);

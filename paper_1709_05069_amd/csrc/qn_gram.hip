@@ -245,7 +245,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_stage1_stream(
     const char *base = static_cast<const char *>(grads);
 
     const int64_t num_tiles = (n + TROWS - 1) / TROWS;
-    const int64_t mine = (num_tiles - blockIdx.x + gridDim.x - 1) / gridDim.x;
+    const int64_t mine = block_tiles(num_tiles, blockIdx.x, gridDim.x);
 
     // Brings tile number k of this block into LDS stage k % 2.
     auto fetch = [&](int64_t k) {

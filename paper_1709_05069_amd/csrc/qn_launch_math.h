@@ -10,6 +10,13 @@
 
 #include "qn.h"
 
+// functions the kernels call too
+#ifdef __HIPCC__
+#define QN_HD __host__ __device__
+#else
+#define QN_HD
+#endif
+
 namespace qn {
 
 // ---- Gram pass ----------------------------------------------------------------
@@ -72,6 +79,13 @@ constexpr int gram_blocks_per_cu(int lds_bytes)
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 inline bool gram_is_small(int64_t n) { return n <= kGramSmallRows; }
+
+// Tiles are dealt round-robin: block b of `grid` takes tiles b, b + grid, ...;
+// this is how many it gets.
+QN_HD inline int64_t block_tiles(int64_t tiles, int64_t block, int64_t grid)
+{
+    return (tiles - block + grid - 1) / grid;
+}
 
 // Blocks of the streaming pass: one per tile up to what fits the device at once,
 // never more than the partials buffer holds.
@@ -146,6 +160,14 @@ struct ApplyPlan {
     int grid;
     int steps;      // staged only: lane-steps per thread and slab
 };
+
+// The staged kernel: block b owns slabs b, b + grid, ... of `slab` lane-steps
+// (a lane-step is R rows); the number of lane-steps of the slab at `base` that exist.
+QN_HD inline int64_t staged_slab_count(int64_t nvec, int64_t base, int64_t slab)
+{
+    const int64_t left = nvec - base;
+    return left < slab ? left : slab;
+}
 
 inline ApplyPlan apply_plan(int64_t n, int dtype, int cu_count)
 {

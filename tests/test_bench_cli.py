@@ -24,3 +24,23 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_unknown_workload_is_an_error():
     r = _run("--workload", "no_such_workload")
     assert r.returncode != 0
+
+
+def test_counter_traffic_is_reported_only_for_unchanged_kernel_sources(tmp_path, monkeypatch):
+    import json
+    sys.path.insert(0, ROOT)
+    import bench
+    h = bench.source_hash("apply_kernel")
+    assert len(h) == 16 and h == bench.source_hash("apply_kernel")
+    rec = {"workload": "gpt2_small", "n": 10, "m": 2, "storage": "f32", "kernel": "apply_kernel",
+           "fetched_bytes": 100, "written_bytes": 20, "source_sha16": h}
+    f = tmp_path / "t.txt"
+    f.write_text(json.dumps({"records": [rec]}))
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(f))
+    assert bench.measured_traffic("gpt2_small", 10, 2, "f32", "apply_kernel") == 120
+    assert bench.measured_traffic("gpt2_small", 11, 2, "f32", "apply_kernel") is None
+    rec["source_sha16"] = "0" * 16            # the kernel has changed since the counters were taken
+    f.write_text(json.dumps({"records": [rec]}))
+    assert bench.measured_traffic("gpt2_small", 10, 2, "f32", "apply_kernel") is None
+    monkeypatch.setattr(bench, "TRAFFIC_FILE", str(tmp_path / "missing.txt"))
+    assert bench.measured_traffic("gpt2_small", 10, 2, "f32", "apply_kernel") is None
