@@ -219,6 +219,43 @@ int qn_update_noalloc(const void *thetas, const void *grads, int dtype, int64_t 
                       int64_t ld, float tau, float lambda, float *theta_new, int *j_out,
                       qn_stream_t stream);
 
+/* ---- the step after a single worker's Write (Section 2, opening sentence: the
+ * method runs following each Write operation by a Worker, synchronously or not) --
+ * Between such steps the library keeps, in `state` (device memory of
+ * qn_gram_state_bytes() bytes, 8-byte aligned, owned by the caller), the m x m
+ * matrix behind eq. (3)/(4) in a form in which one worker's new gradient changes
+ * one row and column.  After worker k has overwritten its column of grads (and of
+ * thetas), one pass over grads with m multiply-adds per row -- instead of the
+ * m (m + 1) / 2 of the full Gram pass -- brings the state up to date; the eigen
+ * kernel and the apply pass then run as in qn_update.
+ *   qn_gram_state_init_ws  : state from the current grads (one full Gram pass).
+ *   qn_gram_state_write_ws : worker's column of grads has been overwritten since
+ *                            the state was last brought up to date; updates it.
+ *                            Any worker, the same one repeatedly, in any order.
+ *   qn_gram_state_get      : C = G^T G and w = G^T g_bar (as qn_gram writes them)
+ *                            of the matrix the state describes.
+ *   qn_update_async_ws     : qn_gram_state_write_ws for `worker`, then j, c and
+ *                            theta_new = theta_bar - tau (g_bar + (Theta - G) c)
+ *                            for the current thetas and grads: the whole server
+ *                            step after that worker's Write.
+ * The state describes grads as of the last init/write; if several columns changed,
+ * call qn_gram_state_write_ws once per changed worker (or init again).  n, m,
+ * dtype and ld must be those of the init call.  workspace as for qn_update_ws.
+ * The state's sums are fp64 over exact differences, so C from it agrees with
+ * qn_gram to the latter's 1e-7. */
+size_t qn_gram_state_bytes(void);
+int qn_gram_state_init_ws(const void *grads, int dtype, int64_t n, int m, int64_t ld,
+                          void *state, void *workspace, size_t workspace_bytes,
+                          qn_stream_t stream);
+int qn_gram_state_write_ws(const void *grads, int dtype, int64_t n, int m, int64_t ld,
+                           int worker, void *state, void *workspace, size_t workspace_bytes,
+                           qn_stream_t stream);
+int qn_gram_state_get(const void *state, int m, double *C, double *w, qn_stream_t stream);
+int qn_update_async_ws(const void *thetas, const void *grads, int dtype, int64_t n, int m,
+                       int64_t ld, int worker, float tau, float lambda, void *state,
+                       float *theta_new, int *j_out, void *workspace, size_t workspace_bytes,
+                       qn_stream_t stream);
+
 /* ---- the operator of eq. (3)/(4) on an arbitrary vector ---------------------
  *   out = Hinv z = z_perp + sum_{k<=j} alpha_k sigma_k^-1 y_k,  alpha_k = z^T u_k,
  * identity on span{u_1..u_j}^perp and the secant inverse (G v_k -> Theta v_k) on

@@ -19,6 +19,12 @@ SIGNATURES = {
                             _vp, _sz, _vp]),
     "qn_update_noalloc": (_int, [_vp, _vp, _int, _i64, _int, _i64, _f32, _f32, _vp, _vp,
                                  _vp]),
+    "qn_gram_state_bytes": (_sz, []),
+    "qn_gram_state_init_ws": (_int, [_vp, _int, _i64, _int, _i64, _vp, _vp, _sz, _vp]),
+    "qn_gram_state_write_ws": (_int, [_vp, _int, _i64, _int, _i64, _int, _vp, _vp, _sz, _vp]),
+    "qn_gram_state_get": (_int, [_vp, _int, _vp, _vp, _vp]),
+    "qn_update_async_ws": (_int, [_vp, _vp, _int, _i64, _int, _i64, _int, _f32, _f32, _vp,
+                                  _vp, _vp, _vp, _sz, _vp]),
     "qn_gram_ws": (_int, [_vp, _int, _i64, _int, _i64, _vp, _vp, _vp, _sz, _vp]),
     "qn_hinv_ws": (_int, [_vp, _vp, _int, _vp, _i64, _int, _i64, _f32, _vp, _vp,
                           _vp, _sz, _vp]),

@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqn.so")
 SOURCES = ["qn_api.hip", "qn_gram.hip", "qn_eig.hip", "qn_apply.hip", "qn_hinv.hip", "qn_bound.hip",
-           "qn_probe.hip"]
+           "qn_probe.hip", "qn_state.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -128,6 +128,25 @@ inline int gram_max_partials(int64_t n, int m, int dtype, int cu_count)
     return best;
 }
 
+// ---- single-column Gram pass (the step after one worker's Write) ----------------
+// Lane = rows; a block partial is column_mp(m) + 1 doubles in the partials buffer.
+constexpr int kColThreads = 256;
+constexpr int kColBlocksPerCu = 2;              // what the kernel's register budget lets run at once
+constexpr int column_mp(int m)
+{
+    return m <= 4 ? 4 : (m <= 8 ? 8 : (m <= 16 ? 16 : (m <= 32 ? 32 : 64)));
+}
+inline int column_pass_grid(int64_t n, int m, int dtype, int cu_count, int max_partials)
+{
+    const int R = dtype == QN_F32 ? 4 : 8;
+    const int64_t want = ceil_div(n, static_cast<int64_t>(kColThreads) * R);
+    int64_t cap = static_cast<int64_t>(cu_count) * kColBlocksPerCu;
+    const int64_t room = static_cast<int64_t>(max_partials) * gram_entries(m) / (column_mp(m) + 1);
+    if (cap > room)
+        cap = room;
+    return static_cast<int>(want < cap ? want : cap);
+}
+
 // ---- apply pass ---------------------------------------------------------------
 constexpr int kApplyThreads = 256;
 #ifndef QN_STAGED_THREADS_F32

@@ -25,6 +25,24 @@ __device__ __forceinline__ int raw_index(int k, int l)
     return (tile * 4 + (i & 3)) * 64 + (i >> 2) * 16 + j;
 }
 
+// Q[k][l], k >= l, from the reduced accumulators: the kReduceRows rows of the
+// two-level reduction added in order and, when `pack` row blocks share the tile
+// (m <= 16 / pack), the partial Gram matrices of those blocks added too.
+__device__ __forceinline__ double raw_entry(const double *__restrict__ mraw, int entries,
+                                            int pack, int k, int l)
+{
+    const int mp = 16 / pack;
+    double q = 0.0;
+    for (int b = 0; b < pack; ++b) {
+        const int at = raw_index(b * mp + k, b * mp + l);
+        double part = 0.0;
+        for (int r = 0; r < kReduceRows; ++r)
+            part += mraw[r * entries + at];
+        q += part;
+    }
+    return q;
+}
+
 // What the projection needs besides the matrix N itself (LDS).
 struct ProjectScratch {
     double rowsum[QN_MAX_M], u[QN_MAX_M];

@@ -145,6 +145,53 @@ def qn_gram(grads, C=None, w=None, stream=None, workspace=None):
     return C, w
 
 
+class GramState:
+    """The m x m state of the step after single-worker Writes (qn_gram_state_*).
+    Holds the device buffer; tied to the (m, n) worker matrix it was made from."""
+
+    def __init__(self, grads, stream=None):
+        L = _lib.load()
+        self.dt, self.m, self.n, self.ld = _worker(grads, "grads")
+        self.buf = torch.empty(int(L.qn_gram_state_bytes()), dtype=torch.uint8, device=grads.device)
+        ws, ws_bytes = _workspace(grads.device, stream)
+        _check(L.qn_gram_state_init_ws(grads.data_ptr(), self.dt, self.n, self.m, self.ld,
+                                       self.buf.data_ptr(), ws, ws_bytes, _stream(stream)),
+               "qn_gram_state_init")
+
+    def _same(self, t, name):
+        if _worker(t, name) != (self.dt, self.m, self.n, self.ld):
+            raise QnError(f"{name} does not match the matrix the state was made from")
+
+    def write(self, grads, worker, stream=None):
+        """worker's row of grads has been overwritten: bring the state up to date."""
+        self._same(grads, "grads")
+        ws, ws_bytes = _workspace(grads.device, stream)
+        _check(_lib.load().qn_gram_state_write_ws(
+            grads.data_ptr(), self.dt, self.n, self.m, self.ld, int(worker),
+            self.buf.data_ptr(), ws, ws_bytes, _stream(stream)), "qn_gram_state_write")
+
+    def gram(self, stream=None):
+        """(C, w) of the matrix the state describes, as qn_gram returns them."""
+        C = torch.empty((self.m, self.m), dtype=torch.float64, device=self.buf.device)
+        w = torch.empty(self.m, dtype=torch.float64, device=self.buf.device)
+        _check(_lib.load().qn_gram_state_get(self.buf.data_ptr(), self.m, C.data_ptr(),
+                                             w.data_ptr(), _stream(stream)), "qn_gram_state_get")
+        return C, w
+
+    def update(self, thetas, grads, worker, tau, lam, theta_new=None, j_out=None, stream=None):
+        """The whole server step after worker's Write.  Returns (theta_new, j_out)."""
+        self._same(thetas, "thetas")
+        self._same(grads, "grads")
+        theta_new = _dev_out(theta_new, (self.n,), torch.float32, thetas.device, "theta_new")
+        j_out = _dev_out(j_out, (1,), torch.int32, thetas.device, "j_out")
+        ws, ws_bytes = _workspace(thetas.device, stream)
+        _check(_lib.load().qn_update_async_ws(
+            thetas.data_ptr(), grads.data_ptr(), self.dt, self.n, self.m, self.ld, int(worker),
+            float(tau), float(lam), self.buf.data_ptr(), theta_new.data_ptr(),
+            j_out.data_ptr(), ws, ws_bytes, _stream(stream)), "qn_update_async")
+        return theta_new, j_out
+
+
 GRAM_AUTO, GRAM_STREAM, GRAM_SMALL = 0, 1, 2
 
 
