@@ -27,7 +27,23 @@ constexpr int kEigMaxSweeps = 30;
 // several of the (M/2)^2 blocks of a round; measured best: 512 threads at M = 48
 // (359 us against 384 with 1024), 256 at M = 64 (709 us against 832 with 1024).
 // Up to M = 8 one wavefront holds every block (25 us against 30 with four).
-template <int M> constexpr int eig_threads() { return M <= 8 ? 64 : (M == 48 ? 512 : 256); }
+// M = 16: the 64 blocks of a round are one wavefront's worth (50 us against 54)
+#ifndef QN_EIG_THREADS_16
+#define QN_EIG_THREADS_16 64
+#endif
+#ifndef QN_EIG_THREADS_24
+#define QN_EIG_THREADS_24 256
+#endif
+#ifndef QN_EIG_THREADS_32
+#define QN_EIG_THREADS_32 256
+#endif
+template <int M> constexpr int eig_threads()
+{
+    return M <= 8 ? 64
+                  : (M == 16 ? QN_EIG_THREADS_16
+                             : (M == 24 ? QN_EIG_THREADS_24
+                                        : (M == 32 ? QN_EIG_THREADS_32 : (M == 48 ? 512 : 256))));
+}
 // dynamic LDS: two copies of the matrix and the eigenvectors, leading dimension M + 1
 template <int M> constexpr int eig_lds_bytes() { return 3 * M * (M + 1) * static_cast<int>(sizeof(double)); }
 
@@ -144,8 +160,9 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
         // from the raw accumulators: C lands in A[0], w in wv; the second copy of
         // the matrix is free to serve as the projection's work space
         __shared__ ProjectScratch sc;
+        __shared__ double red[gram_entries(M)];
         project_raw<kEigThreads>(
-            mraw, entries, m, z_mode, pack, &A[1][0][0], LD, sc,
+            mraw, entries, m, z_mode, pack, &A[1][0][0], LD, red, sc,
             [&](int k, int l, double v) { A[0][k][l] = v; },
             [&](int k, double v) { wv[k] = v; });
     }

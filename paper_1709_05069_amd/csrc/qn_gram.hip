@@ -524,9 +524,10 @@ __global__ __launch_bounds__(kProjectThreads) void gram_project(
     double *__restrict__ C, double *__restrict__ w)
 {
     __shared__ double N[QN_MAX_M * (QN_MAX_M + 1)];
+    __shared__ double red[kMaxEntries];
     __shared__ ProjectScratch sc;
     project_raw<kProjectThreads>(
-        mraw, entries, m, z_mode, pack, N, QN_MAX_M + 1, sc,
+        mraw, entries, m, z_mode, pack, N, QN_MAX_M + 1, red, sc,
         [&](int k, int l, double v) { C[l * m + k] = v; },
         [&](int k, double v) { w[k] = v; });
 }

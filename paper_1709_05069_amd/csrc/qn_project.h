@@ -53,23 +53,35 @@ struct ProjectScratch {
 // `entries` accumulators.  pack > 1 (m <= 16 / pack): the raw tile holds `pack`
 // diagonal blocks of 16 / pack rows and columns, partial results for disjoint
 // row sets, which are added.  N: m rows of leading dimension ldn in LDS
-// (scratch).  On return (after a barrier) put_C(k, l, value) has been called for
-// every entry of C and put_w(k, value) for every entry of w, each by one thread.
+// (scratch); red: `entries` doubles in LDS (scratch).  On return (after a
+// barrier) put_C(k, l, value) has been called for every entry of C and
+// put_w(k, value) for every entry of w, each by one thread.
 template <int THREADS, typename PutC, typename PutW>
 __device__ __forceinline__ void project_raw(const double *__restrict__ mraw, int entries,
                                             int m, int z_mode, int pack, double *N, int ldn,
-                                            ProjectScratch &sc, PutC put_C, PutW put_w)
+                                            double *red, ProjectScratch &sc, PutC put_C,
+                                            PutW put_w)
 {
     const int tid = threadIdx.x;
     const int mp = 16 / pack;        // only used when pack > 1
-    // Q[k][l], k >= l: the rows of the two-level reduction added in order
-    auto raw = [&](int k, int l) {
-        const int at = raw_index(k, l);
-        double q = 0.0;
+    // The rows of the two-level reduction added in order, entry by entry, into
+    // LDS: consecutive threads read consecutive addresses and every thread's
+    // loads are independent, so this costs one trip to memory instead of one
+    // per matrix entry.
+    for (int at = tid; at < entries; at += THREADS) {
+        double v[kReduceRows];
+#pragma unroll
         for (int r = 0; r < kReduceRows; ++r)
-            q += mraw[r * entries + at];
-        return q;
-    };
+            v[r] = mraw[r * entries + at];
+        double q = 0.0;
+#pragma unroll
+        for (int r = 0; r < kReduceRows; ++r)
+            q += v[r];
+        red[at] = q;
+    }
+    __syncthreads();
+    // Q[k][l], k >= l
+    auto raw = [&](int k, int l) { return red[raw_index(k, l)]; };
     for (int e = tid; e < m * m; e += THREADS) {
         const int k = e / m, l = e % m;
         double q = 0.0;
