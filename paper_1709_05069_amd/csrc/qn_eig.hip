@@ -14,9 +14,9 @@
 //     reading the current copy of the matrix and writing the other copy
 //     (double buffering removes the read/write hazard inside a round);
 //   * the same thread applies J_a to two rows of the eigenvector matrix.
-// Reciprocals and reciprocal square roots come from the hardware estimates
-// refined by Newton steps to full double precision; the matrix is pre-scaled by
-// a power of two so that squares cannot overflow or vanish.
+// Reciprocal square roots come from the hardware estimate refined by Newton steps
+// to full double precision; the matrix is pre-scaled by a power of two so that
+// squares cannot overflow or vanish.
 #include "qn_internal.h"
 #include "qn_project.h"
 
@@ -83,15 +83,7 @@ __device__ __forceinline__ double block_max(double v, double *scratch)
     return r;
 }
 
-// 1/x and 1/sqrt(x) to double precision: hardware estimate + Newton steps.
-__device__ __forceinline__ double fast_rcp(double x)
-{
-    double r = __builtin_amdgcn_rcp(x);
-    r = fma(fma(-x, r, 1.0), r, r);
-    r = fma(fma(-x, r, 1.0), r, r);
-    return r;
-}
-
+// 1/sqrt(x) to double precision: hardware estimate + Newton steps.
 __device__ __forceinline__ double fast_rsqrt(double x)
 {
     double r = __builtin_amdgcn_rsq(x);
@@ -104,8 +96,13 @@ __device__ __forceinline__ double fast_rsqrt(double x)
 }
 
 // Plane rotation J = [[c, s], [-s, c]] that annihilates the (p, q) entry of a
-// symmetric matrix: t = tan(theta) is the smaller root of t^2 + 2 zeta t - 1
-// with zeta = (aqq - app) / (2 apq).
+// symmetric matrix: theta with tan(2 theta) = 2 apq / (aqq - app), |theta| <= pi/4
+// (t = tan(theta) is the smaller root of t^2 + 2 zeta t - 1, zeta = (aqq - app) /
+// (2 apq)).  From the half-angle formulas, with hyp = sqrt((aqq - app)^2 + 4 apq^2):
+//     cos(2 theta) = |aqq - app| / hyp,   c = sqrt(X),  X = (1 + cos(2 theta)) / 2,
+//     s = sgn(aqq - app) apq / (hyp c).
+// Two reciprocal square roots (of hyp^2 and of X, which lies in [1/2, 1]) and no
+// division: the shortest dependent chain found for the critical path of a round.
 __device__ __forceinline__ void rotation(double app, double aqq, double apq,
                                          double &c, double &s)
 {
@@ -116,11 +113,11 @@ __device__ __forceinline__ void rotation(double app, double aqq, double apq,
         const double h2 = fma(delta, delta, twice * twice);
         if (!(h2 > 1e-290))      // both far below the scaled matrix norm
             return;
-        const double hyp = h2 * fast_rsqrt(h2);                  // sqrt(h2)
-        const double den = delta + copysign(hyp, delta);
-        const double t = twice * fast_rcp(den);
-        c = fast_rsqrt(fma(t, t, 1.0));
-        s = t * c;
+        const double r = fast_rsqrt(h2);                         // 1 / hyp
+        const double X = fma(fabs(delta), 0.5 * r, 0.5);
+        const double rc = fast_rsqrt(X);                         // 1 / c
+        c = X * rc;
+        s = copysign(1.0, delta) * apq * r * rc;
     }
 }
 

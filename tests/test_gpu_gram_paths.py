@@ -80,6 +80,13 @@ def test_whole_step_with_n_of_the_order_of_m(m, n, lam, seed):
     gr_np = (a[None, :] * th_np - b[None, :]
              + (0.01 * rng.standard_normal((m, n))).astype(np.float32)).astype(np.float32)
     tau = 1.0
+    rank = min(m - 1, n)
+    # "same j" needs a cutoff that no singular value sits at: move lambda off it
+    sig = np.linalg.svd(gr_np.astype(np.float64) - gr_np.astype(np.float64).mean(0), compute_uv=False)
+    for _ in range(20):
+        if np.min(np.abs(sig[:rank] / sig[0] - np.float32(lam))) >= 1e-3:
+            break
+        lam *= 0.83
     lam32 = np.float32(lam)
     lit = oracle.update_literal(th_np, gr_np, tau, lam32)       # eq. (4) with explicit u_k, y_k
     ref = oracle.update_streaming(th_np, gr_np, tau, lam32)     # closed form: also c and w
@@ -87,9 +94,7 @@ def test_whole_step_with_n_of_the_order_of_m(m, n, lam, seed):
     assert rel(ref["theta_new"], lit["theta_new"]) <= 1e-9
     ref["theta_new"] = lit["theta_new"]
     sig = ref["sigma"]
-    rank = min(m - 1, n)
-    if np.min(np.abs(sig[:rank] / sig[0] - lam32)) < 1e-4:
-        pytest.skip("a singular value sits at the cutoff: j is not well posed")
+    assert np.min(np.abs(sig[:rank] / sig[0] - lam32)) > 1e-4
     th, gr = torch.tensor(th_np, device=DEV), torch.tensor(gr_np, device=DEV)
     out, j = qn.qn_update(th, gr, tau, lam)
     assert int(j.item()) == ref["j"]
