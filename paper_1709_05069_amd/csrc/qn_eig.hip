@@ -106,19 +106,17 @@ __device__ __forceinline__ double fast_rsqrt(double x)
 __device__ __forceinline__ void rotation(double app, double aqq, double apq,
                                          double &c, double &s)
 {
-    c = 1.0;
-    s = 0.0;
-    if (apq != 0.0) {
-        const double delta = aqq - app, twice = 2.0 * apq;
-        const double h2 = fma(delta, delta, twice * twice);
-        if (!(h2 > 1e-290))      // both far below the scaled matrix norm
-            return;
-        const double r = fast_rsqrt(h2);                         // 1 / hyp
-        const double X = fma(fabs(delta), 0.5 * r, 0.5);
-        const double rc = fast_rsqrt(X);                         // 1 / c
-        c = X * rc;
-        s = copysign(1.0, delta) * apq * r * rc;
-    }
+    // Branch-free: a vanishing pair (apq = 0 with app = aqq, or both far below the
+    // scaled matrix norm) takes the identity by selection.  apq = 0 alone gives
+    // X = 1, c = 1, s = 0 through the formulas.
+    const double delta = aqq - app, twice = 2.0 * apq;
+    const double h2 = fma(delta, delta, twice * twice);
+    const bool ok = h2 > 1e-290;
+    const double r = fast_rsqrt(ok ? h2 : 1.0);                  // 1 / hyp
+    const double X = fma(fabs(delta), 0.5 * r, 0.5);
+    const double rc = fast_rsqrt(X);                             // 1 / c
+    c = ok ? X * rc : 1.0;
+    s = ok ? copysign(1.0, delta) * apq * r * rc : 0.0;
 }
 
 // Input: C and w in memory, or (C == nullptr) the raw accumulators of the Gram
@@ -237,14 +235,23 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
     // Measured: 5-8 % faster at M = 8 and 32, slower where a thread holds several
     // blocks or M/2 is not a power of two (M = 24, 48, 64), which read in place.
     constexpr bool PREFETCH = BPT == 1 && (NP & (NP - 1)) == 0;
+    // One block per thread: its operands are fetched before the rotation arithmetic
+    // (measured 4-9 % faster at M = 8 .. 32; with several blocks per thread, M = 48
+    // and 64, the extra live registers and LDS queueing cost more than they save).
+    constexpr bool HOIST = BPT == 1;
     const int pr = lane % NP;        // every wavefront: lane l computes the rotation of pair l mod NP
+    // Row offsets (index * LD) rather than indices are carried from round to round:
+    // the multiplications then sit in the prefetch, off the critical path.
+    double *const Ab = &A[0][0][0];
+    double *const Vb = &V[0][0];
     int rp = sp[0][pr], rq = sq[0][pr];
-    int p1[BPT], q1[BPT], p2[BPT], q2[BPT];
+    int rpo = rp * LD, rqo = rq * LD;
+    int p1o[BPT], q1o[BPT], p2[BPT], q2[BPT];
 #pragma unroll
     for (int i = 0; i < BPT; ++i) {
         const int blk = tid + i * kEigThreads;
         const int pa = (blk / NP) % NP, pb = blk % NP;
-        p1[i] = sp[0][pa]; q1[i] = sq[0][pa];
+        p1o[i] = sp[0][pa] * LD; q1o[i] = sq[0][pa] * LD;
         p2[i] = sp[0][pb]; q2[i] = sq[0][pb];
     }
     for (int sweep = 0; sweep < kEigMaxSweeps; ++sweep) {
@@ -258,71 +265,93 @@ __global__ __launch_bounds__(eig_threads<M>()) void eig_select(
             break;
 
         for (int round = 0; round < ROUNDS; ++round) {
-            // PREFETCH: the indices of round + 1; otherwise those of this round
-            const int nr = PREFETCH ? (round + 1 < ROUNDS ? round + 1 : 0) : round;
-            const int rp_n = sp[nr][pr], rq_n = sq[nr][pr];
-            int p1_n[BPT], q1_n[BPT], p2_n[BPT], q2_n[BPT];
-#pragma unroll
-            for (int i = 0; i < BPT; ++i) {
-                const int blk = tid + i * kEigThreads;
-                const int pa = (blk / NP) % NP, pb = blk % NP;
-                p1_n[i] = sp[nr][pa]; q1_n[i] = sq[nr][pa];
-                p2_n[i] = sp[nr][pb]; q2_n[i] = sq[nr][pb];
-            }
-            if constexpr (!PREFETCH) {
-                rp = rp_n;
-                rq = rq_n;
+            const double *const Ac = Ab + cur * (M * LD);
+            double *const An = Ab + (cur ^ 1) * (M * LD);
+            if constexpr (!PREFETCH) {       // the indices of this round, in place
+                rp = sp[round][pr]; rq = sq[round][pr];
+                rpo = rp * LD; rqo = rq * LD;
 #pragma unroll
                 for (int i = 0; i < BPT; ++i) {
-                    p1[i] = p1_n[i]; q1[i] = q1_n[i];
-                    p2[i] = p2_n[i]; q2[i] = q2_n[i];
+                    const int blk = tid + i * kEigThreads;
+                    const int pa = (blk / NP) % NP, pb = blk % NP;
+                    p1o[i] = sp[round][pa] * LD; q1o[i] = sq[round][pa] * LD;
+                    p2[i] = sp[round][pb]; q2[i] = sq[round][pb];
                 }
             }
-            double rc, rs;
-            // all three entries are fetched together (left to itself the compiler
-            // reads the diagonal only after testing the off-diagonal entry: one more
-            // LDS round trip on the critical path of every round)
-            double app = A[cur][rp][rp], aqq = A[cur][rq][rq], apq = A[cur][rp][rq];
+            // The three entries of this lane's pair first, then (HOIST) the operands
+            // of this thread's block, which do not depend on the rotations: their
+            // trip to LDS overlaps the rotation arithmetic.  (Left to itself the
+            // compiler reads the diagonal only after testing the off-diagonal entry,
+            // and the block operands only after the rotation: two more LDS round
+            // trips on the critical path of every round.)
+            double app = Ac[rpo + rp], aqq = Ac[rqo + rq], apq = Ac[rpo + rq];
+            asm volatile("" ::: "memory");      // these three are issued first
+            double b00[BPT], b01[BPT], b10[BPT], b11[BPT], vp0[BPT], vq0[BPT], vp1[BPT], vq1[BPT];
+            auto load_block = [&](int i) {
+                const int pb = (tid + i * kEigThreads) % NP;
+                // the indices are in range also for the idle tail (blk >= NP * NP)
+                b00[i] = Ac[p1o[i] + p2[i]]; b01[i] = Ac[p1o[i] + q2[i]];
+                b10[i] = Ac[q1o[i] + p2[i]]; b11[i] = Ac[q1o[i] + q2[i]];
+                // V <- V J_a on rows 2*pb, 2*pb + 1
+                vp0[i] = Vb[p1o[i] + 2 * pb]; vq0[i] = Vb[q1o[i] + 2 * pb];
+                vp1[i] = Vb[p1o[i] + 2 * pb + 1]; vq1[i] = Vb[q1o[i] + 2 * pb + 1];
+            };
+            if constexpr (HOIST)
+                load_block(0);
+            // PREFETCH: the indices of round + 1
+            [[maybe_unused]] int rp_n = 0, rq_n = 0, p1_n[BPT], q1_n[BPT], p2_n[BPT], q2_n[BPT];
+            if constexpr (PREFETCH) {
+                const int nr = round + 1 < ROUNDS ? round + 1 : 0;
+                rp_n = sp[nr][pr]; rq_n = sq[nr][pr];
+#pragma unroll
+                for (int i = 0; i < BPT; ++i) {
+                    const int blk = tid + i * kEigThreads;
+                    const int pa = (blk / NP) % NP, pb = blk % NP;
+                    p1_n[i] = sp[nr][pa]; q1_n[i] = sq[nr][pa];
+                    p2_n[i] = sp[nr][pb]; q2_n[i] = sq[nr][pb];
+                }
+            }
+            asm volatile("" ::: "memory");      // the loads above stay above
             asm volatile("" : "+v"(app), "+v"(aqq), "+v"(apq));
+            double rc, rs;
             rotation(app, aqq, apq, rc, rs);
 #pragma unroll
             for (int i = 0; i < BPT; ++i) {
                 const int blk = tid + i * kEigThreads;
                 const int pa = blk / NP, pb = blk % NP;      // this block's pair indices
-                // pa < NP also for the idle tail, so the shuffles stay in range
+                // pa % NP < NP also for the idle tail, so the shuffles stay in range
                 const double c1 = __shfl(rc, pa % NP), s1 = __shfl(rs, pa % NP);
                 const double c2 = __shfl(rc, pb), s2 = __shfl(rs, pb);
+                if constexpr (!HOIST)
+                    load_block(i);
                 if (blk < NP * NP) {
-                    const double b00 = A[cur][p1[i]][p2[i]], b01 = A[cur][p1[i]][q2[i]];
-                    const double b10 = A[cur][q1[i]][p2[i]], b11 = A[cur][q1[i]][q2[i]];
-                    // V <- V J_a on rows 2*pb, 2*pb + 1
-                    const double vp0 = V[p1[i]][2 * pb], vq0 = V[q1[i]][2 * pb];
-                    const double vp1 = V[p1[i]][2 * pb + 1], vq1 = V[q1[i]][2 * pb + 1];
                     // B <- J_a^T B J_b
-                    const double t00 = c1 * b00 - s1 * b10, t01 = c1 * b01 - s1 * b11;
-                    const double t10 = s1 * b00 + c1 * b10, t11 = s1 * b01 + c1 * b11;
+                    const double t00 = c1 * b00[i] - s1 * b10[i], t01 = c1 * b01[i] - s1 * b11[i];
+                    const double t10 = s1 * b00[i] + c1 * b10[i], t11 = s1 * b01[i] + c1 * b11[i];
                     double n00 = c2 * t00 - s2 * t01, n01 = s2 * t00 + c2 * t01;
                     double n10 = c2 * t10 - s2 * t11, n11 = s2 * t10 + c2 * t11;
                     if (pa == pb) {   // the annihilated pair: exactly diagonal
                         n01 = 0.0;
                         n10 = 0.0;
                     }
-                    A[cur ^ 1][p1[i]][p2[i]] = n00;
-                    A[cur ^ 1][p1[i]][q2[i]] = n01;
-                    A[cur ^ 1][q1[i]][p2[i]] = n10;
-                    A[cur ^ 1][q1[i]][q2[i]] = n11;
-                    V[p1[i]][2 * pb] = c1 * vp0 - s1 * vq0;
-                    V[q1[i]][2 * pb] = s1 * vp0 + c1 * vq0;
-                    V[p1[i]][2 * pb + 1] = c1 * vp1 - s1 * vq1;
-                    V[q1[i]][2 * pb + 1] = s1 * vp1 + c1 * vq1;
+                    An[p1o[i] + p2[i]] = n00;
+                    An[p1o[i] + q2[i]] = n01;
+                    An[q1o[i] + p2[i]] = n10;
+                    An[q1o[i] + q2[i]] = n11;
+                    Vb[p1o[i] + 2 * pb] = c1 * vp0[i] - s1 * vq0[i];
+                    Vb[q1o[i] + 2 * pb] = s1 * vp0[i] + c1 * vq0[i];
+                    Vb[p1o[i] + 2 * pb + 1] = c1 * vp1[i] - s1 * vq1[i];
+                    Vb[q1o[i] + 2 * pb + 1] = s1 * vp1[i] + c1 * vq1[i];
                 }
             }
-            rp = rp_n;
-            rq = rq_n;
+            if constexpr (PREFETCH) {
+                rp = rp_n; rq = rq_n;
+                rpo = rp * LD; rqo = rq * LD;
 #pragma unroll
-            for (int i = 0; i < BPT; ++i) {
-                p1[i] = p1_n[i]; q1[i] = q1_n[i];
-                p2[i] = p2_n[i]; q2[i] = q2_n[i];
+                for (int i = 0; i < BPT; ++i) {
+                    p1o[i] = p1_n[i] * LD; q1o[i] = q1_n[i] * LD;
+                    p2[i] = p2_n[i]; q2[i] = q2_n[i];
+                }
             }
             __syncthreads();
             cur ^= 1;
