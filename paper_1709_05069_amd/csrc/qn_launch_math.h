@@ -161,6 +161,9 @@ constexpr int kApplyThreads = 256;
 #ifndef QN_STAGED_LDS_KB
 #define QN_STAGED_LDS_KB 128
 #endif
+#ifndef QN_STAGED_MIN_SLABS
+#define QN_STAGED_MIN_SLABS 1
+#endif
 constexpr int kStagedLdsBytes = QN_STAGED_LDS_KB * 1024;
 constexpr int staged_threads(int dtype)
 {
@@ -206,7 +209,7 @@ inline ApplyPlan apply_plan(int64_t n, int dtype, int cu_count)
     // large problems: one block per compute unit with LDS-staged output bursts
     // (a full slab covers 32768 rows; worth it once every unit gets at least one)
     const int64_t slab_rows = kStagedLdsBytes / 4;
-    if (vec && n >= slab_rows * cu_count) {
+    if (vec && n >= slab_rows * cu_count * QN_STAGED_MIN_SLABS) {
         p.shape = kApplyStaged;
         p.grid = cu_count * QN_STAGED_BLOCKS_PER_CU;
         // slab length: every block gets the same number of (nearly) full slabs
