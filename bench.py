@@ -107,6 +107,10 @@ def main():
                          "of them up to 124M rows x 32 workers (about a minute on one "
                          "core), a proportionate prefix of larger workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-write", action="store_true",
+                    help="time the step after a single worker's Write (persistent Gram "
+                         "state + one-column pass, qn_update_async_ws) instead of qn_update; "
+                         "the writing worker cycles through 1, 2, ...")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 4 GiB device copy (a kernel of "
                          "known traffic, for scaling rocprofv3 byte counters)")
@@ -145,8 +149,18 @@ def main():
     theta_new = torch.empty(wl.n, dtype=torch.float32, device="cuda:0")
     j_out = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     qn.qn_init()
+    if args.per_write:
+        state = qn.GramState(grads)
+        turn = [0]
+
+        def one_update():
+            turn[0] = turn[0] % (wl.m - 1) + 1 if wl.m > 1 else 0
+            state.update(thetas, grads, turn[0], wl.tau, wl.lam, theta_new, j_out)
+    else:
+        def one_update():
+            qn.qn_update(thetas, grads, wl.tau, wl.lam, theta_new, j_out)
     for _ in range(args.warmup):
-        qn.qn_update(thetas, grads, wl.tau, wl.lam, theta_new, j_out)
+        one_update()
     torch.cuda.synchronize()
 
     if args.calibrate_copy:
@@ -163,7 +177,7 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            qn.qn_update(thetas, grads, wl.tau, wl.lam, theta_new, j_out)
+            one_update()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -240,7 +254,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: n={wl.n}, m={wl.m}, "
                                f"{wl.storage} storage, lambda={wl.lam}, tau={wl.tau}",
-                   "j": j},
+                   "j": j,
+                   "step": ("after a single worker's Write (qn_update_async_ws)"
+                            if args.per_write else "qn_update")},
         "regions": {"count": REGIONS, "steps_each": args.steps, "ms_per_step": region_ms,
                     "ms_per_step_with_kernel_events": traced_ms,
                     "value_is": "median", "value_min": 1e3 / max(region_ms),

@@ -254,30 +254,40 @@ __global__ __launch_bounds__(kColThreads) void gram_column_pass(
     }
 }
 
-// Row and column `worker` of N and t[worker] from the block partials, added in
-// block order.
+// Row and column `worker` of N and t[worker] from the block partials, in a fixed
+// order: thread (slice, l) adds the partials slice, slice + S, ... of entry l, then
+// the S slices are added in order.
 __global__ __launch_bounds__(kStateThreads) void state_finalize(
     const double *__restrict__ partials, int grid, int mp, int m, int worker, void *state)
 {
     const StateView st = state_view(state);
     const int pivot = st.head[0];
-    for (int l = threadIdx.x; l <= mp; l += kStateThreads) {
-        if (l < mp && l >= m)
-            continue;
-        // eight loads in flight, added in block order (the order fixes the bits)
+    const int width = mp + 1;
+    const int S = kStateThreads / width;                 // >= 3 (width <= 65)
+    __shared__ double part[kStateThreads];
+    const int l = threadIdx.x % width, slice = threadIdx.x / width;
+    if (slice < S) {
+        // eight loads in flight, added in order (the order fixes the bits)
         double v = 0.0;
-        int b = 0;
-        for (; b + 8 <= grid; b += 8) {
+        int b = slice;
+        for (; b + 7 * S < grid; b += 8 * S) {
             double p8[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                p8[i] = partials[static_cast<int64_t>(b + i) * (mp + 1) + l];
+                p8[i] = partials[static_cast<int64_t>(b + i * S) * width + l];
 #pragma unroll
             for (int i = 0; i < 8; ++i)
                 v += p8[i];
         }
-        for (; b < grid; ++b)
-            v += partials[static_cast<int64_t>(b) * (mp + 1) + l];
+        for (; b < grid; b += S)
+            v += partials[static_cast<int64_t>(b) * width + l];
+        part[slice * width + l] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < width && (l == mp || l < m)) {
+        double v = 0.0;
+        for (int sl = 0; sl < S; ++sl)
+            v += part[sl * width + l];
         if (l == mp) {
             st.t[worker] = worker == pivot ? 0.0 : v;
         } else {

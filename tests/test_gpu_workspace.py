@@ -156,3 +156,40 @@ def test_library_owned_workspace_gives_the_same_bits_and_survives_shutdown():
     torch.cuda.synchronize()
     assert torch.equal(h, h2) and torch.equal(w, w2) and torch.equal(b, b2) and torch.equal(tb, t2)
     assert torch.equal(C, C2) and torch.equal(wg, wg2)
+
+
+def test_two_host_threads_with_their_own_workspaces_and_streams():
+    # the *_ws entry points keep no shared state: two host threads, each with its own
+    # stream and workspace, submit steps at the same time and get the serial bits
+    import threading
+    L = _lib.load()
+    cases = [_inputs(1_500_000, "gpt2_small", seed=11), _inputs(2_000_003, "resnet50", seed=12)]
+    serial = [qn.qn_update(th, gr, wl.tau, wl.lam) for wl, th, gr in cases]
+    torch.cuda.synchronize()
+    results, errors = [None, None], []
+
+    def work(i):
+        try:
+            torch.cuda.set_device(0)
+            wl, th, gr = cases[i]
+            stream = torch.cuda.Stream()
+            ws = torch.empty(qn.workspace_bytes(wl.n, wl.m), dtype=torch.uint8, device=DEV)
+            out = torch.empty(wl.n, dtype=torch.float32, device=DEV)
+            j = torch.zeros(1, dtype=torch.int32, device=DEV)
+            torch.cuda.synchronize()
+            for _ in range(20):
+                rc = _raw_update_ws(L, th, gr, wl, out, j, ws.data_ptr(), ws.numel(), stream)
+                assert rc == 0
+            stream.synchronize()
+            results[i] = (out, j)
+        except Exception as e:            # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for (out, j), (ref, jr) in zip(results, serial):
+        assert torch.equal(out, ref) and int(j.item()) == int(jr.item())
