@@ -220,7 +220,8 @@ int qn_update_noalloc(const void *thetas, const void *grads, int dtype, int64_t 
                       qn_stream_t stream);
 
 /* ---- the step after a single worker's Write (Section 2, opening sentence: the
- * method runs following each Write operation by a Worker, synchronously or not) --
+ * server recomputes its step whenever one worker has written its pair, whether the
+ * workers are synchronised or not) ------------------------------------------------
  * Between such steps the library keeps, in `state` (device memory of
  * qn_gram_state_bytes() bytes, 8-byte aligned, owned by the caller), the m x m
  * matrix behind eq. (3)/(4) in a form in which one worker's new gradient changes

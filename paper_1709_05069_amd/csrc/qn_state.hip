@@ -1,5 +1,6 @@
-// The server step after a single worker's Write (Section 2, opening: the method
-// runs "following each Write operation by a Worker", synchronously or not).
+// The server step after a single worker's Write (Section 2, opening: the server
+// recomputes its step whenever one worker has written its pair, whether the
+// workers are synchronised or not).
 //
 // When one worker's pair (theta_k, grad_k) changes, one column of the gradient
 // matrix changes.  The m x m matrix behind eq. (3)/(4) is kept between calls in
