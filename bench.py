@@ -116,7 +116,7 @@ def main():
                          "known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no "
+        print("bench.py: the library runs on one GPU only (no sharding, no "
               "collectives); run with --gpus 1", file=sys.stderr)
         return 2
 
