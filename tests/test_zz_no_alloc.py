@@ -77,3 +77,41 @@ def test_no_alloc_entry_point_checks_its_arguments():
     # every valid problem fits the static array on this device
     assert max(L.qn_workspace_bytes(1 << 40, m, dt) for m in (16, 32, 48, 64)
                for dt in (0, 1, 2)) <= 6 * 1024 * 1024
+
+
+def test_no_alloc_entry_point_under_hip_graph_capture():
+    # the caller this entry point is for: a captured stream may not allocate.  Every
+    # replay, with eager work of the same library between replays, gives the eager bits
+    L = _lib.load()
+    wl, th, gr = _states("resnet50", 300_000, 16, 4)
+    out = torch.empty(wl.n, dtype=torch.float32, device=DEV)
+    j = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ref = torch.empty_like(out)
+    jr = torch.zeros_like(j)
+    assert _call(L.qn_update_ex, th, gr, wl, ref, jr) == 0
+
+    def enqueue():
+        m, n = th.shape
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        return L.qn_update_noalloc(th.data_ptr(), gr.data_ptr(), 0, n, m, th.stride(0), wl.tau,
+                                   wl.lam, out.data_ptr(), j.data_ptr(), stream)
+
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        assert enqueue() == 0                     # set-up happens outside the capture
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        rc = enqueue()
+    assert rc == 0
+    other = torch.empty_like(out)
+    for rep in range(3):
+        out.zero_()
+        j.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref) and int(j.item()) == int(jr.item())
+        wl2, th2, gr2 = _states("small_mlp", 50_000 + rep, 8, 5 + rep)   # dirties the shared scratch
+        assert _call(L.qn_update_noalloc, th2, gr2, wl2, other[:wl2.n], jr.clone()) == 0
