@@ -285,7 +285,7 @@ __global__ __launch_bounds__(kStateThreads) void state_finalize(
         part[slice * width + l] = v;
     }
     __syncthreads();
-    if (threadIdx.x < width && (l == mp || l < m)) {
+    if (static_cast<int>(threadIdx.x) < width && (l == mp || l < m)) {
         double v = 0.0;
         for (int sl = 0; sl < S; ++sl)
             v += part[sl * width + l];
