@@ -38,9 +38,15 @@ typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef v4f v4f_elem __attribute__((aligned(4)));
 typedef v4u v4u_elem __attribute__((aligned(2)));
 
-// worker columns whose loads are issued together (two such chunks are in flight)
+// worker columns whose loads are issued together (two such chunks are in flight),
+// by storage type, launch shape and compiled-in worker count.  Measured on MI355X,
+// chunks of 4 against 8, fp32 storage: in the staged kernel at n = 124M m = 16:
+// 2.54 vs 2.63 ms, m = 32: 4.83 vs 4.88 ms, m = 8 and 64: no difference, and with
+// the worker count known only at run time (m = 24, 48) chunks of 4 are 6 % slower;
+// in the direct kernel (n = 8M) chunks of 4 are 2 % slower.  16-bit storage is
+// indifferent.
 #ifndef QN_APPLY_CHUNK_F32
-#define QN_APPLY_CHUNK_F32 8
+#define QN_APPLY_CHUNK_F32(STAGED, MC) (((STAGED) && ((MC) == 16 || (MC) == 32)) ? 4 : 8)
 #endif
 #ifndef QN_APPLY_CHUNK_BF16
 #define QN_APPLY_CHUNK_BF16 2
@@ -78,8 +84,8 @@ __device__ __forceinline__ Acc coef_sum(const float *__restrict__ c,
         s += coef_at<Acc>(c, c64, k);
     return s;
 }
-template <int DT> struct ApplyChunk {
-    static constexpr int value = DT == QN_F32 ? QN_APPLY_CHUNK_F32 : QN_APPLY_CHUNK_BF16;
+template <int DT, int MC, bool STAGED> struct ApplyChunk {
+    static constexpr int value = DT == QN_F32 ? QN_APPLY_CHUNK_F32(STAGED, MC) : QN_APPLY_CHUNK_BF16;
 };
 
 // One load of R rows of a column kept as it arrives (16 bytes, or one element),
@@ -151,7 +157,7 @@ __device__ __forceinline__ void load_vec(const void *base, int64_t elem, float (
 }
 
 // theta_new for rows [row, row + R), from every worker column.
-template <int DT, int MC, int R>
+template <int DT, int MC, int R, bool STAGED>
 __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
                                              const void *__restrict__ grads,
                                              int64_t row, int m_rt, int64_t ld,
@@ -162,7 +168,7 @@ __device__ __forceinline__ void compute_rows(const void *__restrict__ thetas,
                                              float tau, float inv_m,
                                              float (&res)[R])
 {
-    constexpr int kApplyChunk = ApplyChunk<DT>::value;
+    constexpr int kApplyChunk = ApplyChunk<DT, MC, STAGED>::value;
     // 16-bit storage: the inputs carry 8 or 11 significant bits, so plain fp32 sums of the
     // stored values (St = sum theta_k, acc = sum c_k (theta_k - g_k), error about
     // 1e-7 of the values) are far inside the data's own resolution and save a
@@ -269,7 +275,7 @@ __device__ __forceinline__ void apply_rows(const void *__restrict__ thetas,
                                            float *__restrict__ out)
 {
     float res[R];
-    compute_rows<DT, MC, R>(thetas, grads, row, m_rt, ld, c, c64, z, csum, tau, inv_m, res);
+    compute_rows<DT, MC, R, false>(thetas, grads, row, m_rt, ld, c, c64, z, csum, tau, inv_m, res);
     if constexpr (R == 1) {
         out[row] = res[0];
     } else {
@@ -349,7 +355,7 @@ __global__ __launch_bounds__(StagedThreads<DT>::value) void apply_staged(
             const int64_t v = base + static_cast<int64_t>(it) * kStagedThreads + threadIdx.x;
             if (v < nvec) {
                 float res[R];
-                compute_rows<DT, MC, R>(thetas, grads, v * R, m_rt, ld, c, c64, z, csum, tau, inv_m, res);
+                compute_rows<DT, MC, R, true>(thetas, grads, v * R, m_rt, ld, c, c64, z, csum, tau, inv_m, res);
 #pragma unroll
                 for (int h = 0; h < Q; ++h)
                     stage[(it * kStagedThreads + threadIdx.x) * Q + h] =
