@@ -50,6 +50,16 @@ int qn_probe_copy(const void *src, void *dst, int64_t bytes, qn_stream_t stream)
 int qn_probe_read(const void *src, int64_t bytes, float *sink, qn_stream_t stream);
 int qn_probe_sink_floats(void);
 
+/* ---- latency probe --------------------------------------------------------------
+ * One wavefront runs `links` dependent fp64 multiply-adds (a positive multiple
+ * of 8, at most 2^30) and times them inside the kernel.  out (device, 3 values):
+ * out[0] = ticks of the constant 100 MHz counter, out[1] = ticks of the shader's
+ * cycle counter over the same interval, out[2] = no meaning.  The chain takes a
+ * fixed number of shader clocks, so out[0] follows the clock the device runs at
+ * when the probe is launched -- the quantity the one-workgroup eigen kernel's
+ * duration depends on. */
+int qn_probe_chain(int64_t links, unsigned long long *out, qn_stream_t stream);
+
 /* ---- qn_gram_ex with the stage-1 kernel named by the caller --------------------
  * qn_gram_ex picks its kernel from n: the fp64 vector kernel up to 16384 rows,
  * the matrix-core streaming pass above.  Both are correct at every n >= 1; this

@@ -12,6 +12,6 @@ from . import synth  # noqa: F401
 from .qn import (qn_update, qn_update_noalloc, qn_gram, qn_eig, qn_apply, qn_init,  # noqa: F401
                  qn_hinv, qn_gemv_t, qn_coef, qn_hinv_apply,
                  qn_update_bounded, qn_tau_bound, BOUND_SIGMA1, BOUND_SECANT,
-                 trace_begin, trace_end, probe_copy, probe_read, diag_gram,
+                 trace_begin, trace_end, probe_copy, probe_read, probe_chain, diag_gram,
                  workspace_bytes, GramState, GRAM_AUTO, GRAM_STREAM, GRAM_SMALL,
                  KERNEL_NAMES, QnError)

@@ -61,6 +61,7 @@ SIGNATURES = {
     "qn_tau_bound": (_int, [_vp, _vp, _vp, _vp, _int, _f32, _int, _vp, _vp, _vp]),
     "qn_probe_copy": (_int, [_vp, _vp, _i64, _vp]),
     "qn_probe_read": (_int, [_vp, _i64, _vp, _vp]),
+    "qn_probe_chain": (_int, [_i64, _vp, _vp]),
     "qn_probe_sink_floats": (_int, []),
     "qn_trace_begin": (_int, [_int]),
     "qn_trace_end": (_int, [_vp, _vp]),

@@ -1,6 +1,10 @@
 // Bandwidth probes: a plain 128-bit grid-stride copy and a read-only sum.
 // They move a known number of bytes, so they calibrate hardware byte counters
 // and give the streaming ceiling the Gram and apply passes are compared with.
+// And a latency probe: one wavefront running a chain of dependent fp64
+// multiply-adds, timed inside the kernel by the constant-rate counter; its
+// duration follows the shader clock, which is what the one-workgroup eigen
+// kernel is bound by.
 #include "qn_internal.h"
 
 namespace qn {
@@ -44,6 +48,29 @@ __global__ __launch_bounds__(kProbeThreads) void probe_read(
         (acc.x + acc.y) + (acc.z + acc.w);
 }
 
+// out[0]: ticks of the constant 100 MHz counter over `links` dependent fp64
+// multiply-adds, out[1]: the same interval by the shader's own cycle counter,
+// out[2]: the chain's value (keeps it alive).
+__global__ __launch_bounds__(64) void probe_chain(int64_t links, double seed,
+                                                  unsigned long long *__restrict__ out)
+{
+    double x = seed + threadIdx.x;
+    const double a = 1.0 - 1.0 / 1048576.0, b = 1.0 / 1024.0;
+    const unsigned long long w0 = wall_clock64(), c0 = clock64();
+#pragma unroll 1
+    for (int64_t i = 0; i < links; i += 8) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            x = fma(x, a, b);
+    }
+    const unsigned long long w1 = wall_clock64(), c1 = clock64();
+    if (threadIdx.x == 0) {
+        out[0] = w1 - w0;
+        out[1] = c1 - c0;
+        out[2] = static_cast<unsigned long long>(__double_as_longlong(x));
+    }
+}
+
 }  // namespace qn
 
 using namespace qn;
@@ -84,6 +111,19 @@ int qn_probe_read(const void *src, int64_t bytes, float *sink, qn_stream_t strea
     hipLaunchKernelGGL(probe_read, dim3(grid), dim3(kProbeThreads), 0,
                        static_cast<hipStream_t>(stream),
                        static_cast<const v4f *>(src), nvec, sink);
+    return check_launch();
+}
+
+int qn_probe_chain(int64_t links, unsigned long long *out, qn_stream_t stream)
+{
+    if (!out || links < 8 || links % 8 != 0 || links > (static_cast<int64_t>(1) << 30))
+        return QN_EINVAL;
+    Device *dev = nullptr;
+    const int rc = get_device(&dev);
+    if (rc != QN_OK)
+        return rc;
+    hipLaunchKernelGGL(probe_chain, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream),
+                       links, 0.5, out);
     return check_launch();
 }
 

@@ -381,6 +381,16 @@ def probe_read(src, stream=None):
     return sink
 
 
+def probe_chain(links, out=None, stream=None):
+    """Enqueues the latency probe; returns the device tensor (3 x int64) holding
+    100 MHz ticks, shader-counter ticks and a value of no meaning."""
+    if out is None:
+        out = torch.zeros(3, dtype=torch.int64, device="cuda")
+    _check(_lib.load().qn_probe_chain(int(links), out.data_ptr(), _stream(stream)),
+           "qn_probe_chain")
+    return out
+
+
 def trace_begin(max_launches: int = 4096):
     _check(_lib.load().qn_trace_begin(int(max_launches)), "qn_trace_begin")
 

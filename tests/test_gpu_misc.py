@@ -70,6 +70,20 @@ def test_probes_move_the_bytes_they_claim():
         qn.probe_copy(src[:1001], dst[:1001])          # not a multiple of 16 bytes
 
 
+def test_latency_probe_times_its_chain():
+    short = qn.probe_chain(8 * 1000)
+    long = qn.probe_chain(8 * 4000)
+    torch.cuda.synchronize()
+    t_short, t_long = int(short[0].item()), int(long[0].item())
+    assert t_short > 0 and int(short[1].item()) > 0
+    # four times the links: four times the time (dependent chain, nothing else)
+    assert 3.0 <= t_long / t_short <= 5.0
+    # 8000 dependent fp64 multiply-adds at a few clocks each: tens of microseconds
+    assert 1e-6 <= t_short / 100e6 <= 1e-3
+    with pytest.raises(qn.QnError):
+        qn.probe_chain(7)
+
+
 def test_binding_rejects_bad_tensors():
     wl, th, gr = _inputs(5_000, "small_mlp")
     with pytest.raises(qn.QnError):
