@@ -131,16 +131,25 @@ inline int gram_max_partials(int64_t n, int m, int dtype, int cu_count)
 // ---- single-column Gram pass (the step after one worker's Write) ----------------
 // Lane = rows; a block partial is column_mp(m) + 1 doubles in the partials buffer.
 constexpr int kColThreads = 256;
-constexpr int kColBlocksPerCu = 2;              // what the kernel's register budget lets run at once
 constexpr int column_mp(int m)
 {
     return m <= 4 ? 4 : (m <= 8 ? 8 : (m <= 16 ? 16 : (m <= 32 ? 32 : 64)));
+}
+// Blocks per compute unit.  A lane keeps 2 + min(8, m) (+ 8 above m = 8) 16-byte
+// loads in flight and the pass streams best with 70 ... 100 KB in flight per unit;
+// more is slower, not faster.  Measured at n = 124M, fp32 storage, blocks per unit
+// 1 / 2 / 4: m = 32: 2.25 / 2.36 / 2.49 ms, m = 16: 1.14 / 1.20 / 1.22, m = 8: 0.61 /
+// 0.60 / 0.65, m = 4: 0.81 / 0.47 / 0.34, m = 2: - / 0.23 / 0.17; 16-bit storage at
+// m = 4 (n = 248M): 2 blocks 0.32, 4 blocks 0.33 ms.
+constexpr int column_blocks_per_cu(int m, int dtype)
+{
+    return m > 8 ? 1 : ((m <= 4 && dtype == QN_F32) ? 4 : 2);
 }
 inline int column_pass_grid(int64_t n, int m, int dtype, int cu_count, int max_partials)
 {
     const int R = dtype == QN_F32 ? 4 : 8;
     const int64_t want = ceil_div(n, static_cast<int64_t>(kColThreads) * R);
-    int64_t cap = static_cast<int64_t>(cu_count) * kColBlocksPerCu;
+    int64_t cap = static_cast<int64_t>(cu_count) * column_blocks_per_cu(m, dtype);
     const int64_t room = static_cast<int64_t>(max_partials) * gram_entries(m) / (column_mp(m) + 1);
     if (cap > room)
         cap = room;

@@ -87,6 +87,22 @@ static void check_gram(int64_t n, int m, int dtype, int cu)
         }
 }
 
+// The single-column pass after a Write: its grid fits the device and its block
+// partials (column_mp(m) + 1 doubles each) fit the partials buffer of the workspace.
+static void check_column(int64_t n, int m, int dtype, int cu)
+{
+    const int maxp = gram_max_partials(n, m, dtype, cu);
+    const int grid = column_pass_grid(n, m, dtype, cu, maxp);
+    const int bpc = column_blocks_per_cu(m, dtype);
+    CHECK(bpc >= 1 && bpc <= 8, "blocks per unit %d", bpc);
+    CHECK(grid >= 1 && grid <= (int64_t)cu * bpc, "n=%" PRId64 " m=%d grid=%d", n, m, grid);
+    CHECK((int64_t)grid * (column_mp(m) + 1) <= (int64_t)maxp * gram_entries(m),
+          "n=%" PRId64 " m=%d dt=%d cu=%d grid=%d maxp=%d", n, m, dtype, cu, grid, maxp);
+    const int R = dtype == QN_F32 ? 4 : 8;
+    CHECK(grid <= ceil_div(n, (int64_t)kColThreads * R), "more blocks than row groups");
+    CHECK(column_mp(m) >= m && column_mp(m) <= QN_MAX_M, "mp");
+}
+
 static void check_apply(int64_t n, int dtype, int cu)
 {
     const ApplyPlan p = apply_plan(n, dtype, cu);
@@ -127,8 +143,10 @@ int main()
         for (int cu : kCus) {
             for (int dt = QN_F32; dt <= QN_F16; ++dt) {
                 check_apply(n, dt, cu);
-                for (int m = 1; m <= QN_MAX_M; ++m)
+                for (int m = 1; m <= QN_MAX_M; ++m) {
                     check_gram(n, m, dt, cu);
+                    check_column(n, m, dt, cu);
+                }
             }
         }
     // the reduction's grid: entries / 64 blocks by kReduceRows rows
