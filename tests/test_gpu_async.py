@@ -31,6 +31,14 @@ CASES = [
     ("gpt2_small", 40_000, 64, "f16", [1, 0, 63]),
     ("gpt2_small", 25_007, 20, "f16", [19, 0, 0, 7]),
     ("gpt2_small", 100_000, 1, "f32", [0, 0]),
+    # long enough that the column pass runs with its capped grid (every thread
+    # takes several row groups), for each blocks-per-unit setting
+    ("gpt2_small", 2_000_003, 32, "f32", [7, 0]),
+    ("resnet50", 1_500_001, 16, "f32", [0, 15]),
+    ("small_mlp", 3_000_002, 4, "f32", [3, 0]),
+    ("small_mlp", 2_500_000, 8, "f32", [1]),
+    ("stress_1b_bf16", 3_000_008, 8, "bf16", [0, 5]),
+    ("stress_1b_bf16", 2_000_001, 32, "bf16", [31]),
 ]
 
 
