@@ -173,6 +173,8 @@ APPLY_CASES = [
     ("gpt2_small", 40000, 1), ("stress_1b_bf16", 50000, 32),
     ("stress_1b_bf16", 12345, 8), ("stress_1b_bf16", 8200, 23),
     ("gpt2_small", 30000, 64), ("gpt2_small", 10001, 40), ("stress_1b_bf16", 16008, 64),
+    # the direct kernel with its capped grid (several row groups per thread)
+    ("small_mlp", 3_000_001, 8), ("stress_1b_bf16", 5_000_003, 4),
 ]
 
 
