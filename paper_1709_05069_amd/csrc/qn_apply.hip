@@ -321,8 +321,9 @@ __global__ __launch_bounds__(kApplyThreads) void apply_kernel(
 // it is computed, 0.26 ms when each CU writes 128 KiB bursts).  So one block
 // per CU keeps a slab of results in LDS and writes it out in one contiguous
 // burst.  Same arithmetic, same bits as apply_kernel.
-// block size of the staged variant: fp32 streams best with few waves per CU;
-// 16-bit storage has twice the arithmetic per byte and needs more waves to hide it
+// block size of the staged variant: fp32 streams best with 4 waves per CU (2 are
+// too few: 7.5 vs 4.8 ms); 16-bit storage has twice the arithmetic per byte and
+// takes 8 (16 waves are 0.5 ... 2 % slower at every worker count)
 template <int DT> struct StagedThreads {
     static constexpr int value = staged_threads(DT);
 };

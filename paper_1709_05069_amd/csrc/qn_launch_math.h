@@ -162,7 +162,7 @@ constexpr int kApplyThreads = 256;
 #define QN_STAGED_THREADS_F32 256
 #endif
 #ifndef QN_STAGED_THREADS_BF16
-#define QN_STAGED_THREADS_BF16 1024
+#define QN_STAGED_THREADS_BF16 512
 #endif
 #ifndef QN_STAGED_BLOCKS_PER_CU
 #define QN_STAGED_BLOCKS_PER_CU 1
